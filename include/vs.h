@@ -1,0 +1,154 @@
+/*
+ * vs.h -- C ABI of the vertical-slash sparse prefill library for MI355X (gfx950).
+ *
+ * The method (Qwen2.5-1M technical report, section 5.2, "MInference" and
+ * "Integrating with Chunked prefill" paragraphs): for every query chunk of a
+ * long prompt and every attention head,
+ *   1. estimate  -- attention of the chunk's last 64 queries against all keys
+ *                   seen so far, summed along columns ("vertical lines") and
+ *                   along diagonals pos - j = const ("slash lines");
+ *   2. select    -- keep a per-head number of the best vertical and slash lines;
+ *   3. attend    -- softmax attention over the selected keys only.
+ * A dense causal kernel is the fallback / comparison (the paper's "full
+ * attention").  softmax_lse is an optional output of both attention calls (the
+ * quantity the paper's Attention_Recall is built from).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless the comment says host.  The
+ *    library never allocates, frees or synchronises: work is enqueued on
+ *    `stream` (a hipStream_t passed as void*, NULL = the null stream) and
+ *    VS_OK means "enqueued".  The caller owns every buffer, including the
+ *    workspace, and keeps them alive until the stream reaches the work.
+ *  - Q / K / V / out hold bf16; element strides are given in vs_params, the
+ *    innermost (head_dim) stride is 1.  Base pointers must be 16-byte aligned
+ *    and strides multiples of 8 elements.
+ *  - Keys and values of the current chunk must already be in the cache:
+ *    positions 0 .. q_start + q_len - 1 are read ("all key tokens").
+ *  - Query head h uses key/value head h / (n_q_heads / n_kv_heads).
+ *  - Arguments are validated on the host before any HIP call; a negative
+ *    status is returned and nothing is enqueued.  No exception or abort crosses
+ *    this boundary.  Inputs must be finite.
+ *  - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef VS_H_
+#define VS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  VS_OK = 0,
+  VS_ERR_INVALID_ARG = -1, /* null pointer, bad shape, bad stride, misalignment      */
+  VS_ERR_UNSUPPORTED = -2, /* a valid request this build has no kernel for           */
+  VS_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or too small             */
+  VS_ERR_HIP = -4          /* the HIP runtime refused a launch                       */
+};
+
+/* which workspace size vs_workspace_bytes() reports */
+enum { VS_WS_ESTIMATE = 0, VS_WS_SELECT = 1, VS_WS_SPARSE = 2, VS_WS_DENSE = 3, VS_WS_CHUNK = 4 };
+
+typedef struct vs_params {
+  int32_t n_q_heads;       /* Hq                                                      */
+  int32_t n_kv_heads;      /* Hkv, divides Hq                                         */
+  int32_t head_dim;        /* D: 64 or 128                                            */
+  int32_t last_q;          /* W: estimation window, 1..64 (the paper uses the last 64
+                              tokens of each chunk); effective W' = min(W, q_len)     */
+  int64_t q_len;           /* C: rows of this chunk, >= 1                             */
+  int64_t q_start;         /* s: absolute position of row 0, multiple of `block`;
+                              keys visible n_k = s + C (< 2^31)                       */
+  int64_t q_stride_tok, q_stride_head;   /* Q  [C][Hq][D]     => (Hq*D, D)            */
+  int64_t k_stride_tok, k_stride_head;   /* K  [>=n_k][Hkv][D] => (Hkv*D, D)          */
+  int64_t v_stride_tok, v_stride_head;   /* V  like K                                 */
+  int64_t o_stride_tok, o_stride_head;   /* out like Q                                */
+  float softmax_scale;     /* 1/sqrt(D), or 1/(t sqrt(D)) with YaRN's temperature     */
+  int32_t block;           /* B: edge of the computed slash blocks, must be 64        */
+  int32_t vertical_budget; /* Bv >= 1: vertical lines kept per head, forced included  */
+  int32_t slash_budget;    /* Bs >= 1: slash lines kept per head, forced included     */
+  int32_t keep_first_cols; /* columns 0..keep_first_cols-1 are always kept (>= 0)     */
+  int32_t keep_local_band; /* offsets 0..keep_local_band-1 are always kept (>= 0)     */
+} vs_params;
+
+/* Bytes of workspace the call named by `which` needs for these parameters
+ * (0 on invalid parameters).  Host function; touches no device.  The workspace
+ * must be 256-byte aligned.  VS_WS_CHUNK covers vs_prefill_chunk. */
+size_t vs_workspace_bytes(const vs_params *p, int which);
+
+/* Host: static, NUL-terminated description of a status code. */
+const char *vs_status_string(int status);
+
+/* Host: softmax scale with the attention temperature of the YaRN equation
+ * (section 5.1): 1/(t sqrt(D)) with sqrt(1/t) = 0.1 ln(s) + 1, where s is the
+ * ratio of inference length to training length (s >= 1; s = 1 gives 1/sqrt(D)). */
+float vs_yarn_softmax_scale(float s, int32_t head_dim);
+
+/* Step 1 (section 5.2, MInference paragraph: attention between the last query
+ * tokens and all key tokens; chunked-prefill paragraph: the last 64 tokens of
+ * each chunk).  With P the causal softmax rows of the W' window queries
+ * (chunk rows C-W'..C-1) over keys 0..n_k-1:
+ *   vscore[h][j] = sum_r P[r][j]              column (vertical) score of key j
+ *   sscore[h][o] = sum_r P[r][pos(r) - o]     diagonal (slash) score of offset o
+ *   lse_lastq[h][r] = log sum_j exp(scale q_r.k_j)        (optional, may be NULL)
+ * vscore, sscore: fp32 [Hq][n_k], fully overwritten.  lse_lastq: fp32 [Hq][W'].
+ * Only the window rows of q are read.  Results are run-to-run identical. */
+int vs_estimate(const vs_params *p, const void *q, const void *k, float *vscore,
+                float *sscore, float *lse_lastq, void *ws, size_t ws_bytes,
+                void *stream);
+
+/* Step 2 (section 5.2: critical tokens chosen by the vertical-slash pattern with
+ * a per-head count of vertical and slash lines).  Per head, keeps the
+ * kv = min(Bv, n_k) best columns and ks = min(Bs, n_k) best offsets, where
+ * "best" is the order (score descending, index ascending) with the forced
+ * entries (keep_first_cols, keep_local_band) counted as +infinity.  Scores must
+ * be >= 0 and finite.
+ *   v_idx: int32 [Hq][Bv], s_idx: int32 [Hq][Bs], ascending, tail filled with -1
+ *   v_cnt, s_cnt: int32 [Hq] = kv, ks */
+int vs_select(const vs_params *p, const float *vscore, const float *sscore,
+              int32_t *v_idx, int32_t *v_cnt, int32_t *s_idx, int32_t *s_cnt,
+              void *ws, size_t ws_bytes, void *stream);
+
+/* Step 3 (section 5.2: attention only on the selected critical tokens; section
+ * 5.3.1: sparse K/V loading is what the kernel is tuned for).  The computed mask
+ * widens each slash line to the 64x64 blocks it crosses: with block-diagonal set
+ * A = { floor(o/64) } U { floor(o/64)+1 : o mod 64 != 0 } over the selected
+ * offsets o, row i (position p = s+i) attends key j <= p iff
+ *     j is a selected column   or   floor(p/64) - floor(j/64) is in A.
+ *   out[i][h][:] = sum_j softmax(scale q_i.k_j) V_j over those keys (bf16, fp32
+ *   accumulation), lse[h][i] = log of the softmax denominator (optional fp32
+ *   [Hq][C]; softmax_lse_sparse of the paper).  A row with no key gets 0 / -inf.
+ * v_idx/s_idx/v_cnt/s_cnt as produced by vs_select (ascending, in range). */
+int vs_sparse_attn_prefill(const vs_params *p, const void *q, const void *k,
+                           const void *v, const int32_t *v_idx,
+                           const int32_t *v_cnt, const int32_t *s_idx,
+                           const int32_t *s_cnt, void *out, float *lse, void *ws,
+                           size_t ws_bytes, void *stream);
+
+/* Dense causal attention of the chunk (the paper's full attention, the thing the
+ * sparse path is measured against): every key j <= p.  Same outputs as above;
+ * lse is softmax_lse_full.  Budget fields of p are ignored. */
+int vs_dense_causal_prefill(const vs_params *p, const void *q, const void *k,
+                            const void *v, void *out, float *lse, void *ws,
+                            size_t ws_bytes, void *stream);
+
+/* One chunk of the whole path on one stream, no host synchronisation:
+ * vs_estimate -> vs_select -> vs_sparse_attn_prefill.  Scores and index sets
+ * live in the workspace (VS_WS_CHUNK). */
+int vs_prefill_chunk(const vs_params *p, const void *q, const void *k,
+                     const void *v, void *out, float *lse, void *ws,
+                     size_t ws_bytes, void *stream);
+
+/* Work accounting for a set of index sets: per head, the number of 64x64
+ * (query block, key block) tiles the sparse kernel issues for this chunk
+ * (slash tiles, then vertical tiles of up to 64 gathered columns).
+ *   tiles: int64 [Hq][2] = {slash tiles, vertical tiles}. */
+int vs_count_tiles(const vs_params *p, const int32_t *v_idx, const int32_t *v_cnt,
+                   const int32_t *s_idx, const int32_t *s_cnt, int64_t *tiles,
+                   void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VS_H_ */

@@ -1,0 +1,253 @@
+"""Thin ctypes binding of libvs (include/vs.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels of the library; torch is used here only to
+hold device memory and to name the current stream.  There is no fallback of any kind: if
+the library has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvs.so")
+
+VS_OK = 0
+VS_ERR_INVALID_ARG, VS_ERR_UNSUPPORTED, VS_ERR_WORKSPACE, VS_ERR_HIP = -1, -2, -3, -4
+VS_WS_ESTIMATE, VS_WS_SELECT, VS_WS_SPARSE, VS_WS_DENSE, VS_WS_CHUNK = range(5)
+
+
+class VsParams(C.Structure):
+    """Mirror of `vs_params` in include/vs.h."""
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("last_q", C.c_int32),
+        ("q_len", C.c_int64), ("q_start", C.c_int64),
+        ("q_stride_tok", C.c_int64), ("q_stride_head", C.c_int64),
+        ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
+        ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("o_stride_tok", C.c_int64), ("o_stride_head", C.c_int64),
+        ("softmax_scale", C.c_float), ("block", C.c_int32),
+        ("vertical_budget", C.c_int32), ("slash_budget", C.c_int32),
+        ("keep_first_cols", C.c_int32), ("keep_local_band", C.c_int32),
+    ]
+
+
+class VsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libvs.so (built by paper_2501_15383_amd.build); raises if it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2501_15383_amd.build` "
+                "(there is no CPU or PyTorch fallback for this library)")
+        L = C.CDLL(LIB_PATH)
+        P, vp, sz = C.POINTER(VsParams), C.c_void_p, C.c_size_t
+        L.vs_workspace_bytes.restype = sz
+        L.vs_workspace_bytes.argtypes = [P, C.c_int]
+        L.vs_status_string.restype = C.c_char_p
+        L.vs_status_string.argtypes = [C.c_int]
+        L.vs_yarn_softmax_scale.restype = C.c_float
+        L.vs_yarn_softmax_scale.argtypes = [C.c_float, C.c_int32]
+        L.vs_estimate.restype = C.c_int
+        L.vs_estimate.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_select.restype = C.c_int
+        L.vs_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_sparse_attn_prefill.restype = C.c_int
+        L.vs_sparse_attn_prefill.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_dense_causal_prefill.restype = C.c_int
+        L.vs_dense_causal_prefill.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_prefill_chunk.restype = C.c_int
+        L.vs_prefill_chunk.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_count_tiles.restype = C.c_int
+        L.vs_count_tiles.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
+           "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles"]
+
+
+def status_string(status: int) -> str:
+    return lib().vs_status_string(int(status)).decode()
+
+
+def yarn_softmax_scale(s: float, head_dim: int) -> float:
+    return float(lib().vs_yarn_softmax_scale(float(s), int(head_dim)))
+
+
+@dataclass
+class Chunk:
+    """Parameters of one chunk call; strides are taken from the tensors at call time."""
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    q_len: int
+    q_start: int
+    softmax_scale: float
+    last_q: int = 64
+    block: int = 64
+    vertical_budget: int = 1
+    slash_budget: int = 1
+    keep_first_cols: int = 1
+    keep_local_band: int = 64
+
+    @property
+    def n_k(self) -> int:
+        return self.q_start + self.q_len
+
+    def params(self, q=None, k=None, v=None, out=None) -> VsParams:
+        hq, hkv, d = self.n_q_heads, self.n_kv_heads, self.head_dim
+
+        def st(t, heads):
+            return (t.stride(0), t.stride(1)) if t is not None else (heads * d, d)
+
+        qs, ks, vs_, os_ = st(q, hq), st(k, hkv), st(v, hkv), st(out, hq)
+        return VsParams(hq, hkv, d, self.last_q, self.q_len, self.q_start, qs[0], qs[1], ks[0], ks[1],
+                        vs_[0], vs_[1], os_[0], os_[1], float(self.softmax_scale), self.block,
+                        self.vertical_budget, self.slash_budget, self.keep_first_cols, self.keep_local_band)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, where):
+    if rc != VS_OK:
+        raise VsError(rc, where)
+
+
+def workspace_bytes(ck: Chunk, which: int) -> int:
+    p = ck.params()
+    return int(lib().vs_workspace_bytes(C.byref(p), which))
+
+
+def _ws(ck: Chunk, which: int, device):
+    n = workspace_bytes(ck, which)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device), n
+
+
+def _chk_inner(t, name, d):
+    assert t.dtype == torch.bfloat16 and t.dim() == 3 and t.stride(2) == 1 and t.shape[2] == d, name
+
+
+def estimate(ck: Chunk, q, k, want_lse=False):
+    """vs_estimate.  q: bf16 [C][Hq][D] (the chunk), k: bf16 [>=n_k][Hkv][D].
+    Returns vscore, sscore (fp32 [Hq][n_k]) and lse_lastq (fp32 [Hq][W'] or None)."""
+    _chk_inner(q, "q", ck.head_dim); _chk_inner(k, "k", ck.head_dim)
+    assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k
+    dev = q.device
+    vscore = torch.empty((ck.n_q_heads, ck.n_k), dtype=torch.float32, device=dev)
+    sscore = torch.empty_like(vscore)
+    lse = torch.empty((ck.n_q_heads, min(ck.last_q, ck.q_len)), dtype=torch.float32, device=dev) if want_lse else None
+    ws, n = _ws(ck, VS_WS_ESTIMATE, dev)
+    p = ck.params(q=q, k=k)
+    _check(lib().vs_estimate(C.byref(p), _ptr(q), _ptr(k), _ptr(vscore), _ptr(sscore), _ptr(lse),
+                             _ptr(ws), n, _stream()), "vs_estimate")
+    return vscore, sscore, lse
+
+
+def select(ck: Chunk, vscore, sscore):
+    """vs_select.  Returns v_idx [Hq][Bv], v_cnt [Hq], s_idx [Hq][Bs], s_cnt [Hq] (int32)."""
+    assert vscore.dtype == torch.float32 and vscore.is_contiguous() and vscore.shape == (ck.n_q_heads, ck.n_k)
+    assert sscore.dtype == torch.float32 and sscore.is_contiguous() and sscore.shape == (ck.n_q_heads, ck.n_k)
+    dev = vscore.device
+    v_idx = torch.empty((ck.n_q_heads, ck.vertical_budget), dtype=torch.int32, device=dev)
+    s_idx = torch.empty((ck.n_q_heads, ck.slash_budget), dtype=torch.int32, device=dev)
+    v_cnt = torch.empty(ck.n_q_heads, dtype=torch.int32, device=dev)
+    s_cnt = torch.empty(ck.n_q_heads, dtype=torch.int32, device=dev)
+    ws, n = _ws(ck, VS_WS_SELECT, dev)
+    p = ck.params()
+    _check(lib().vs_select(C.byref(p), _ptr(vscore), _ptr(sscore), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx),
+                           _ptr(s_cnt), _ptr(ws) if n else C.c_void_p(0), n, _stream()), "vs_select")
+    return v_idx, v_cnt, s_idx, s_cnt
+
+
+def _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt):
+    for t in (v_idx, v_cnt, s_idx, s_cnt):
+        assert t.dtype == torch.int32 and t.is_contiguous()
+    assert v_idx.shape == (ck.n_q_heads, ck.vertical_budget) and s_idx.shape == (ck.n_q_heads, ck.slash_budget)
+
+
+def sparse_attn_prefill(ck: Chunk, q, k, v, v_idx, v_cnt, s_idx, s_cnt, want_lse=False, out=None, ws=None):
+    """vs_sparse_attn_prefill.  Returns out bf16 [C][Hq][D] and lse fp32 [Hq][C] (or None)."""
+    for t, nm in ((q, "q"), (k, "k"), (v, "v")):
+        _chk_inner(t, nm, ck.head_dim)
+    assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k and v.shape[0] >= ck.n_k
+    _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt)
+    dev = q.device
+    if out is None:
+        out = torch.empty((ck.q_len, ck.n_q_heads, ck.head_dim), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((ck.n_q_heads, ck.q_len), dtype=torch.float32, device=dev) if want_lse else None
+    n = workspace_bytes(ck, VS_WS_SPARSE)
+    if ws is None:
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
+    p = ck.params(q=q, k=k, v=v, out=out)
+    _check(lib().vs_sparse_attn_prefill(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(v_idx), _ptr(v_cnt),
+                                        _ptr(s_idx), _ptr(s_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
+                                        _stream()), "vs_sparse_attn_prefill")
+    return out, lse
+
+
+def dense_causal_prefill(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None):
+    """vs_dense_causal_prefill.  Returns out bf16 [C][Hq][D] and lse fp32 [Hq][C] (or None)."""
+    for t, nm in ((q, "q"), (k, "k"), (v, "v")):
+        _chk_inner(t, nm, ck.head_dim)
+    assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k and v.shape[0] >= ck.n_k
+    dev = q.device
+    if out is None:
+        out = torch.empty((ck.q_len, ck.n_q_heads, ck.head_dim), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((ck.n_q_heads, ck.q_len), dtype=torch.float32, device=dev) if want_lse else None
+    n = workspace_bytes(ck, VS_WS_DENSE)
+    if ws is None:
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
+    p = ck.params(q=q, k=k, v=v, out=out)
+    _check(lib().vs_dense_causal_prefill(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(ws),
+                                         ws.numel(), _stream()), "vs_dense_causal_prefill")
+    return out, lse
+
+
+def prefill_chunk(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None):
+    """vs_prefill_chunk: estimate -> select -> sparse attention on the current stream."""
+    for t, nm in ((q, "q"), (k, "k"), (v, "v")):
+        _chk_inner(t, nm, ck.head_dim)
+    assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k and v.shape[0] >= ck.n_k
+    dev = q.device
+    if out is None:
+        out = torch.empty((ck.q_len, ck.n_q_heads, ck.head_dim), dtype=torch.bfloat16, device=dev)
+    lse = torch.empty((ck.n_q_heads, ck.q_len), dtype=torch.float32, device=dev) if want_lse else None
+    n = workspace_bytes(ck, VS_WS_CHUNK)
+    if ws is None:
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
+    p = ck.params(q=q, k=k, v=v, out=out)
+    _check(lib().vs_prefill_chunk(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(ws),
+                                  ws.numel(), _stream()), "vs_prefill_chunk")
+    return out, lse
+
+
+def count_tiles(ck: Chunk, v_idx, v_cnt, s_idx, s_cnt):
+    """vs_count_tiles.  Returns int64 [Hq][2] = (slash tiles, vertical tiles) issued for the chunk."""
+    _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt)
+    dev = v_idx.device
+    tiles = torch.empty((ck.n_q_heads, 2), dtype=torch.int64, device=dev)
+    ws, n = _ws(ck, VS_WS_SPARSE, dev)
+    p = ck.params()
+    _check(lib().vs_count_tiles(C.byref(p), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx), _ptr(s_cnt), _ptr(tiles),
+                                _ptr(ws), n, _stream()), "vs_count_tiles")
+    return tiles

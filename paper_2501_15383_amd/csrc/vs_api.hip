@@ -1,0 +1,210 @@
+// Host side of libvs: the extern "C" entry points declared in include/vs.h.  Every argument
+// is checked here, before the first HIP call, so a bad call returns a status without touching
+// a device; the kernels may then assume consistent shapes.
+#include <math.h>
+
+#include "vs_common.h"
+
+namespace vs {
+namespace {
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+bool stride_ok(int64_t tok, int64_t head, int d) {
+  return tok >= d && head >= d && tok % 8 == 0 && head % 8 == 0;
+}
+
+// shape / stride checks common to every entry point
+int check_params(const vs_params* p, bool need_budgets) {
+  if (!p) return VS_ERR_INVALID_ARG;
+  if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads != 0) return VS_ERR_INVALID_ARG;
+  if (p->head_dim < 1 || p->q_len < 1 || p->q_start < 0) return VS_ERR_INVALID_ARG;
+  if (p->block < 1 || p->last_q < 1) return VS_ERR_INVALID_ARG;
+  if (!(p->softmax_scale > 0.f) || !isfinite(p->softmax_scale)) return VS_ERR_INVALID_ARG;
+  if (p->q_start > (int64_t)INT32_MAX || p->q_len > (int64_t)INT32_MAX ||
+      p->q_start + p->q_len > (int64_t)INT32_MAX - 4096)
+    return VS_ERR_INVALID_ARG;
+  if (p->keep_first_cols < 0 || p->keep_local_band < 0) return VS_ERR_INVALID_ARG;
+  if (need_budgets && (p->vertical_budget < 1 || p->slash_budget < 1)) return VS_ERR_INVALID_ARG;
+  if (p->head_dim != 64 && p->head_dim != 128) return VS_ERR_UNSUPPORTED;
+  if (p->block != kBlock) return VS_ERR_UNSUPPORTED;
+  if (p->last_q > 64) return VS_ERR_UNSUPPORTED;
+  if (p->q_start % kBlock != 0) return VS_ERR_UNSUPPORTED;
+  const int d = p->head_dim;
+  if (!stride_ok(p->q_stride_tok, p->q_stride_head, d) || !stride_ok(p->k_stride_tok, p->k_stride_head, d) ||
+      !stride_ok(p->v_stride_tok, p->v_stride_head, d) || !stride_ok(p->o_stride_tok, p->o_stride_head, d))
+    return VS_ERR_INVALID_ARG;
+  return VS_OK;
+}
+
+int check_ws(const void* ws, size_t have, size_t need) {
+  if (need == 0) return VS_OK;
+  if (!ws || !aligned(ws, 256) || have < need) return VS_ERR_WORKSPACE;
+  return VS_OK;
+}
+
+size_t bitmaps_bytes(const vs_params& p, bool dense) {
+  const size_t heads = dense ? 1 : (size_t)p.n_q_heads;
+  return align_up(heads * (size_t)bitmap_words(p.q_start + p.q_len) * sizeof(uint32_t), 256);
+}
+
+size_t sparse_ws_bytes(const vs_params& p, bool dense) { return 2 * bitmaps_bytes(p, dense); }
+
+// layout of the VS_WS_CHUNK workspace
+struct ChunkWs {
+  size_t vscore, sscore, v_idx, s_idx, v_cnt, s_cnt, sub, total;
+};
+ChunkWs chunk_layout(const vs_params& p) {
+  const size_t n_k = (size_t)(p.q_start + p.q_len), hq = (size_t)p.n_q_heads;
+  ChunkWs w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  w.vscore = take(hq * n_k * sizeof(float));
+  w.sscore = take(hq * n_k * sizeof(float));
+  w.v_idx = take(hq * (size_t)p.vertical_budget * sizeof(int32_t));
+  w.s_idx = take(hq * (size_t)p.slash_budget * sizeof(int32_t));
+  w.v_cnt = take(hq * sizeof(int32_t));
+  w.s_cnt = take(hq * sizeof(int32_t));
+  w.sub = off;
+  const size_t a = estimate_ws_bytes(p), b = select_ws_bytes(p), c = sparse_ws_bytes(p, false);
+  off += a > b ? (a > c ? a : c) : (b > c ? b : c);
+  w.total = off;
+  return w;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? VS_OK : VS_ERR_HIP; }
+
+}  // namespace
+}  // namespace vs
+
+using namespace vs;
+
+extern "C" {
+
+size_t vs_workspace_bytes(const vs_params* p, int which) {
+  if (check_params(p, which == VS_WS_SELECT || which == VS_WS_SPARSE || which == VS_WS_CHUNK) != VS_OK) return 0;
+  switch (which) {
+    case VS_WS_ESTIMATE: return estimate_ws_bytes(*p);
+    case VS_WS_SELECT: return select_ws_bytes(*p);
+    case VS_WS_SPARSE: return sparse_ws_bytes(*p, false);
+    case VS_WS_DENSE: return sparse_ws_bytes(*p, true);
+    case VS_WS_CHUNK: return chunk_layout(*p).total;
+    default: return 0;
+  }
+}
+
+const char* vs_status_string(int status) {
+  switch (status) {
+    case VS_OK: return "ok";
+    case VS_ERR_INVALID_ARG: return "invalid argument (null pointer, shape, stride or alignment)";
+    case VS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128, block 64, last_q <= 64, q_start a multiple of 64)";
+    case VS_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
+    case VS_ERR_HIP: return "HIP runtime error at launch";
+    default: return "unknown status";
+  }
+}
+
+float vs_yarn_softmax_scale(float s, int32_t head_dim) {
+  if (!(s >= 1.f) || head_dim < 1) return 0.f;
+  const float r = 0.1f * logf(s) + 1.0f;  // sqrt(1/t)
+  return r * r / sqrtf((float)head_dim);
+}
+
+int vs_estimate(const vs_params* p, const void* q, const void* k, float* vscore, float* sscore,
+                float* lse_lastq, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p, false);
+  if (rc != VS_OK) return rc;
+  if (!q || !k || !vscore || !sscore) return VS_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(vscore, 4) || !aligned(sscore, 4)) return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, estimate_ws_bytes(*p));
+  if (rc != VS_OK) return rc;
+  return hip_status(launch_estimate(*p, q, k, vscore, sscore, lse_lastq, ws, (hipStream_t)stream));
+}
+
+int vs_select(const vs_params* p, const float* vscore, const float* sscore, int32_t* v_idx,
+              int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void* ws, size_t ws_bytes,
+              void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!vscore || !sscore || !v_idx || !v_cnt || !s_idx || !s_cnt) return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, select_ws_bytes(*p));
+  if (rc != VS_OK) return rc;
+  return hip_status(launch_select(*p, vscore, sscore, v_idx, v_cnt, s_idx, s_cnt, ws, (hipStream_t)stream));
+}
+
+int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, const void* v,
+                           const int32_t* v_idx, const int32_t* v_cnt, const int32_t* s_idx,
+                           const int32_t* s_cnt, void* out, float* lse, void* ws, size_t ws_bytes,
+                           void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!q || !k || !v || !out || !v_idx || !v_cnt || !s_idx || !s_cnt) return VS_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
+  if (rc != VS_OK) return rc;
+  uint32_t* bm_a = (uint32_t*)ws;
+  uint32_t* bm_u = (uint32_t*)((char*)ws + bitmaps_bytes(*p, false));
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_build_bitmaps(*p, s_idx, s_cnt, false, bm_a, bm_u, st);
+  if (e != hipSuccess) return VS_ERR_HIP;
+  return hip_status(launch_attention(*p, q, k, v, v_idx, v_cnt, false, bm_a, bm_u, out, lse, st));
+}
+
+int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, const void* v,
+                            void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p, false);
+  if (rc != VS_OK) return rc;
+  if (!q || !k || !v || !out) return VS_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, true));
+  if (rc != VS_OK) return rc;
+  uint32_t* bm_a = (uint32_t*)ws;
+  uint32_t* bm_u = (uint32_t*)((char*)ws + bitmaps_bytes(*p, true));
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_build_bitmaps(*p, nullptr, nullptr, true, bm_a, bm_u, st);
+  if (e != hipSuccess) return VS_ERR_HIP;
+  return hip_status(launch_attention(*p, q, k, v, nullptr, nullptr, true, bm_a, bm_u, out, lse, st));
+}
+
+int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const void* v, void* out,
+                     float* lse, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!q || !k || !v || !out) return VS_ERR_INVALID_ARG;
+  if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
+  const ChunkWs w = chunk_layout(*p);
+  rc = check_ws(ws, ws_bytes, w.total);
+  if (rc != VS_OK) return rc;
+  char* b = (char*)ws;
+  float* vscore = (float*)(b + w.vscore);
+  float* sscore = (float*)(b + w.sscore);
+  int32_t* v_idx = (int32_t*)(b + w.v_idx);
+  int32_t* s_idx = (int32_t*)(b + w.s_idx);
+  int32_t* v_cnt = (int32_t*)(b + w.v_cnt);
+  int32_t* s_cnt = (int32_t*)(b + w.s_cnt);
+  void* sub = b + w.sub;
+  const size_t sub_bytes = w.total - w.sub;
+  rc = vs_estimate(p, q, k, vscore, sscore, nullptr, sub, sub_bytes, stream);
+  if (rc != VS_OK) return rc;
+  rc = vs_select(p, vscore, sscore, v_idx, v_cnt, s_idx, s_cnt, sub, sub_bytes, stream);
+  if (rc != VS_OK) return rc;
+  return vs_sparse_attn_prefill(p, q, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse, sub, sub_bytes, stream);
+}
+
+int vs_count_tiles(const vs_params* p, const int32_t* v_idx, const int32_t* v_cnt,
+                   const int32_t* s_idx, const int32_t* s_cnt, int64_t* tiles, void* ws,
+                   size_t ws_bytes, void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!v_idx || !v_cnt || !s_idx || !s_cnt || !tiles) return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
+  if (rc != VS_OK) return rc;
+  uint32_t* bm_a = (uint32_t*)ws;
+  uint32_t* bm_u = (uint32_t*)((char*)ws + bitmaps_bytes(*p, false));
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_build_bitmaps(*p, s_idx, s_cnt, false, bm_a, bm_u, st);
+  if (e != hipSuccess) return VS_ERR_HIP;
+  return hip_status(launch_count_tiles(*p, v_idx, v_cnt, bm_a, tiles, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,282 @@
+// Estimation for the vertical-slash pattern (section 5.2, MInference paragraph: attention
+// between the last query tokens and all key tokens; chunked-prefill paragraph: the last 64
+// tokens of each chunk).  For the W' <= 64 window rows of every head: causal softmax rows
+// over all n_k keys, summed along columns (vscore) and along diagonals pos - j (sscore).
+//
+// Two sweeps over the K cache, both tiled the same way: a workgroup owns one KV head and a
+// contiguous range of keys; its waves are the query heads of that KV group, so every K
+// tile is fetched from HBM once per sweep for all heads of the group and staged in LDS.
+//   sweep A  per-row running (max, sum) over the range -> partials -> k_estimate_combine -> lse
+//   sweep B  P = exp2(S * scale*log2e - lse2); column sums are stored directly (a column
+//            belongs to exactly one workgroup); diagonal sums are accumulated in an LDS strip
+//            private to the wave, then added to the zero-filled global array (at most two
+//            workgroups touch one offset, and x + y is commutative), so scores are
+//            run-to-run identical.
+// bf16 MFMA (32x32x16) with fp32 accumulation; sweep A uses the K Q^T orientation (a lane
+// owns one query), sweep B the Q K^T orientation (a lane owns one key).
+#include "vs_common.h"
+
+namespace vs {
+
+constexpr int kEstRange = 1024;  // keys per workgroup
+
+struct EstArgs {
+  const __bf16* q;
+  const __bf16* k;
+  int64_t q_stride_tok, q_stride_head, k_stride_tok, k_stride_head;
+  float* vscore;
+  float* sscore;
+  float* lse_lastq;  // optional, natural log
+  float* part;       // [Hq][n_ranges][64][2]  (max, sum) in the base-2 scaled domain
+  float* lse2;       // [Hq][64] base-2 scaled lse (+inf for rows >= W')
+  int32_t n_q_heads, n_kv_heads, group;
+  int32_t wp;        // W'
+  int32_t n_ranges;
+  int64_t q_len, n_k, p0;  // p0: position of window row 0
+  float scale_log2;
+};
+
+template <int D, int NW, int PASS>
+__global__ __launch_bounds__(64 * NW) void k_estimate(const EstArgs a) {
+  constexpr int NT = 64 * NW, KS = D + 8, DCH = D / 8, DSTEPS = D / 16;
+  constexpr int KPT = (64 * DCH + NT - 1) / NT;
+  constexpr int STRIP = kEstRange + 64;
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[64 * KS];
+  __shared__ float strip[PASS == 1 ? NW * STRIP : 1];
+
+  const int rng = blockIdx.x, g = blockIdx.y, hb = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, hh = lane >> 5;
+  const int hin = hb * NW + wv;
+  const bool head_ok = hin < a.group;
+  const int h = g * a.group + (head_ok ? hin : 0);
+  const int64_t ja = (int64_t)rng * kEstRange;
+  const int64_t jb_ = ja + kEstRange < a.n_k ? ja + kEstRange : a.n_k;
+  const int n_tiles = (int)((jb_ - ja + 63) >> 6);
+  const __bf16* kbase = a.k + (int64_t)g * a.k_stride_head;
+
+  // window rows of this head, as MFMA operand: lane (r = 32 ib + lane%32, hh)
+  bf16x8 qreg[2][DSTEPS];
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    int r = 32 * ib + (lane & 31);
+    if (r > a.wp - 1) r = a.wp - 1;
+    const __bf16* qp = a.q + (a.q_len - a.wp + r) * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
+#pragma unroll
+    for (int st = 0; st < DSTEPS; ++st) qreg[ib][st] = *(const bf16x8*)(qp + 16 * st);
+  }
+
+  if (PASS == 1) {
+    for (int x = tid; x < NW * STRIP; x += NT) strip[x] = 0.f;
+  }
+
+  // sweep A state: this lane's (max, sum) for query 32 ib + lane%32 over its half of the keys
+  float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
+  // sweep B: lse2 of the 32 queries this lane meets: i = 32 ib + 8 (x/4) + 4 hh + (x%4)
+  float lse_r[2][16];
+  if (PASS == 1) {
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+      for (int x = 0; x < 16; ++x)
+        lse_r[ib][x] = a.lse2[(int64_t)h * 64 + 32 * ib + 8 * (x >> 2) + 4 * hh + (x & 3)];
+  }
+
+  u32x4 kst[KPT];
+  auto load_tile = [&](int tile) {
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) {
+      const int x = tid + e * NT;
+      if (x < 64 * DCH) {
+        const int r = x / DCH, ch = x % DCH;
+        int64_t j = ja + 64 * tile + r;
+        if (j > a.n_k - 1) j = a.n_k - 1;
+        kst[e] = *(const u32x4*)(kbase + j * a.k_stride_tok + ch * 8);
+      }
+    }
+  };
+  auto store_tile = [&]() {
+#pragma unroll
+    for (int e = 0; e < KPT; ++e) {
+      const int x = tid + e * NT;
+      if (x < 64 * DCH) {
+        const int r = x / DCH, ch = x % DCH;
+        *(u32x4*)&Ks[r * KS + ch * 8] = kst[e];
+      }
+    }
+  };
+
+  load_tile(0);
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    store_tile();
+    __syncthreads();
+    if (tile + 1 < n_tiles) load_tile(tile + 1);
+    const int64_t j0 = ja + 64 * tile;
+    const bool need_mask = j0 + 63 > a.p0;  // some (row, key) of this tile is acausal
+
+    if (head_ok) {
+#pragma unroll
+      for (int jb = 0; jb < 2; ++jb) {
+        bf16x8 kf[DSTEPS];
+#pragma unroll
+        for (int st = 0; st < DSTEPS; ++st)
+          kf[st] = *(const bf16x8*)&Ks[(32 * jb + (lane & 31)) * KS + 16 * st + 8 * hh];
+        float colacc = 0.f;  // sweep B: this lane's column sum over both query halves
+#pragma unroll
+        for (int ib = 0; ib < 2; ++ib) {
+          f32x16 s;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) s[x] = 0.f;
+          if (PASS == 0) {
+            // D[j][i]: lane = query i, element x = key 32 jb + 8 (x/4) + 4 hh + (x%4)
+#pragma unroll
+            for (int st = 0; st < DSTEPS; ++st)
+              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qreg[ib][st], s, 0, 0, 0);
+            const int r = 32 * ib + (lane & 31);
+            if (need_mask) {
+#pragma unroll
+              for (int x = 0; x < 16; ++x) {
+                const int64_t j = j0 + 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
+                if (j > a.p0 + r) s[x] = -INFINITY;
+              }
+            }
+            float mx = s[0];
+#pragma unroll
+            for (int x = 1; x < 16; ++x) mx = fmaxf(mx, s[x]);
+            const float m_new = fmaxf(mrun[ib], mx * a.scale_log2);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            float acc = lrun[ib] * __builtin_amdgcn_exp2f(mrun[ib] - m_use);
+#pragma unroll
+            for (int x = 0; x < 16; ++x)
+              acc += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -m_use));
+            lrun[ib] = acc;
+            mrun[ib] = m_new;
+          } else {
+            // D[i][j]: lane = key j = 32 jb + lane%32, element x = query 32 ib + 8 (x/4) + 4 hh + (x%4)
+#pragma unroll
+            for (int st = 0; st < DSTEPS; ++st)
+              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[ib][st], kf[st], s, 0, 0, 0);
+            const int jl = 64 * tile + 32 * jb + (lane & 31);  // key index inside the range
+            const int64_t j = ja + jl;
+            float colsum = 0.f;
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+              const int i = 32 * ib + 8 * (x >> 2) + 4 * hh + (x & 3);
+              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -lse_r[ib][x]));
+              if (need_mask && j > a.p0 + i) p = 0.f;
+              colsum += p;
+              // offset o = p0 + i - j; strip index = i - jl + (kEstRange - 1) in [0, kEstRange + 62]
+              atomicAdd(&strip[wv * STRIP + i - jl + (kEstRange - 1)], p);
+            }
+            colacc += colsum;
+          }
+        }
+        if (PASS == 1) {
+          colacc += __shfl_xor(colacc, 32);
+          const int64_t j = ja + 64 * tile + 32 * jb + (lane & 31);
+          if (hh == 0 && j < a.n_k) a.vscore[(int64_t)h * a.n_k + j] = colacc;
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (!head_ok) return;
+  if (PASS == 0) {
+    // merge the two key halves of each query, then one partial per (head, range, row)
+#pragma unroll
+    for (int ib = 0; ib < 2; ++ib) {
+      const float m2 = __shfl_xor(mrun[ib], 32), l2 = __shfl_xor(lrun[ib], 32);
+      const float M = fmaxf(mrun[ib], m2);
+      const float Mu = (M == -INFINITY) ? 0.f : M;
+      const float L = lrun[ib] * __builtin_amdgcn_exp2f(mrun[ib] - Mu) + l2 * __builtin_amdgcn_exp2f(m2 - Mu);
+      if (hh == 0) {
+        float* pp = a.part + (((int64_t)h * a.n_ranges + rng) * 64 + 32 * ib + (lane & 31)) * 2;
+        pp[0] = M;
+        pp[1] = L;
+      }
+    }
+  } else {
+    // strip index x <-> offset o = p0 - ja - (kEstRange - 1) + x
+    const int64_t o0 = a.p0 - ja - (kEstRange - 1);
+    for (int x = lane; x < STRIP; x += 64) {
+      const int64_t o = o0 + x;
+      const float val = strip[wv * STRIP + x];
+      if (o >= 0 && o < a.n_k && val != 0.f) atomicAdd(&a.sscore[(int64_t)h * a.n_k + o], val);
+    }
+  }
+}
+
+// lse2[h][r] = M + log2(L) over all range partials; rows >= W' get +inf (their P is 0).
+__global__ __launch_bounds__(64) void k_estimate_combine(const EstArgs a) {
+  const int h = blockIdx.x, r = threadIdx.x;
+  float M = -INFINITY, L = 0.f;
+  for (int rg = 0; rg < a.n_ranges; ++rg) {
+    const float* pp = a.part + (((int64_t)h * a.n_ranges + rg) * 64 + r) * 2;
+    const float m = pp[0], l = pp[1];
+    const float Mn = fmaxf(M, m);
+    const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
+    L = L * __builtin_amdgcn_exp2f(M - Mu) + l * __builtin_amdgcn_exp2f(m - Mu);
+    M = Mn;
+  }
+  const float l2 = M + __builtin_amdgcn_logf(L);
+  a.lse2[(int64_t)h * 64 + r] = r < a.wp ? l2 : INFINITY;
+  if (a.lse_lastq && r < a.wp) a.lse_lastq[(int64_t)h * a.wp + r] = l2 * kLn2;
+}
+
+__global__ __launch_bounds__(256) void k_fill_zero(float* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+static int pick_waves(int group) {
+  const int cand[] = {1, 2, 4, 5, 7, 8};
+  for (int c : cand)
+    if (c >= group) return c;
+  return 8;
+}
+
+size_t estimate_ws_bytes(const vs_params& p) {
+  const int64_t n_k = p.q_start + p.q_len;
+  const int64_t n_ranges = ceil_div(n_k, kEstRange);
+  return align_up((size_t)p.n_q_heads * n_ranges * 64 * 2 * sizeof(float), 256) +
+         align_up((size_t)p.n_q_heads * 64 * sizeof(float), 256);
+}
+
+template <int D, int NW>
+static hipError_t launch_est(const EstArgs& a, int hb, hipStream_t st) {
+  const dim3 grid(a.n_ranges, a.n_kv_heads, hb);
+  hipLaunchKernelGGL((k_estimate<D, NW, 0>), grid, dim3(64 * NW), 0, st, a);
+  hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(64), 0, st, a);
+  hipLaunchKernelGGL((k_estimate<D, NW, 1>), grid, dim3(64 * NW), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_estimate(const vs_params& p, const void* q, const void* k, float* vscore,
+                           float* sscore, float* lse_lastq, void* ws, hipStream_t st) {
+  EstArgs a;
+  a.q = (const __bf16*)q; a.k = (const __bf16*)k;
+  a.q_stride_tok = p.q_stride_tok; a.q_stride_head = p.q_stride_head;
+  a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
+  a.vscore = vscore; a.sscore = sscore; a.lse_lastq = lse_lastq;
+  a.n_q_heads = p.n_q_heads; a.n_kv_heads = p.n_kv_heads; a.group = p.n_q_heads / p.n_kv_heads;
+  a.wp = (int32_t)(p.last_q < p.q_len ? p.last_q : p.q_len);
+  a.q_len = p.q_len; a.n_k = p.q_start + p.q_len; a.p0 = a.n_k - a.wp;
+  a.n_ranges = (int32_t)ceil_div(a.n_k, kEstRange);
+  a.scale_log2 = p.softmax_scale * kLog2e;
+  a.part = (float*)ws;
+  a.lse2 = (float*)((char*)ws + align_up((size_t)p.n_q_heads * a.n_ranges * 64 * 2 * sizeof(float), 256));
+  const int64_t n_sc = (int64_t)p.n_q_heads * a.n_k;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(n_sc / 1024 < 1 ? 1 : (n_sc / 1024 > 8192 ? 8192 : n_sc / 1024))),
+                     dim3(256), 0, st, sscore, n_sc);
+  const int nw = pick_waves(a.group);
+  const int hb = (int)ceil_div(a.group, nw);
+#define VS_EST_CASE(DD, WW) \
+  if (p.head_dim == DD && nw == WW) return launch_est<DD, WW>(a, hb, st);
+  VS_EST_CASE(128, 1) VS_EST_CASE(128, 2) VS_EST_CASE(128, 4) VS_EST_CASE(128, 5)
+  VS_EST_CASE(128, 7) VS_EST_CASE(128, 8)
+  VS_EST_CASE(64, 1) VS_EST_CASE(64, 2) VS_EST_CASE(64, 4) VS_EST_CASE(64, 5)
+  VS_EST_CASE(64, 7) VS_EST_CASE(64, 8)
+#undef VS_EST_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace vs

@@ -1,0 +1,144 @@
+// Selection of the vertical and slash lines (section 5.2, MInference paragraph: critical
+// tokens are chosen by the vertical-slash pattern with a per-head count of vertical and
+// diagonal lines).  One workgroup per (head, kind) problem: exact top-k of up to 2^31 fp32
+// scores without sorting.
+//   1. forced entries (the lowest `keep` indices) are taken first;
+//   2. a most-significant-digit radix select (4 x 8 bits on an order-preserving integer image
+//      of the float) finds the threshold key T and how many entries equal to T are needed;
+//   3. one ordered compaction pass emits indices in ascending order: every key > T, and the
+//      lowest-index keys == T (ties go to the lower index).  Ranks come from wave ballots and
+//      a 16-entry cross-wave scan, all integer, so the result is exact and deterministic.
+#include "vs_common.h"
+
+namespace vs {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSelItems = 8;  // elements per lane per compaction step
+
+__device__ __forceinline__ uint32_t order_key(float x) {
+  const uint32_t b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+struct SelArgs {
+  const float* vscore;
+  const float* sscore;
+  int64_t n;  // n_k
+  int32_t v_budget, s_budget, keep_v, keep_s;
+  int32_t* v_idx;
+  int32_t* v_cnt;
+  int32_t* s_idx;
+  int32_t* s_cnt;
+};
+
+__global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
+  const int h = blockIdx.x, kind = blockIdx.y;
+  const int64_t n = a.n;
+  const float* sc = (kind ? a.sscore : a.vscore) + (int64_t)h * n;
+  const int budget = kind ? a.s_budget : a.v_budget;
+  const int keep = kind ? a.keep_s : a.keep_v;
+  int32_t* out = (kind ? a.s_idx : a.v_idx) + (int64_t)h * budget;
+  const int k = budget < n ? budget : (int)n;
+  const int f = keep < k ? keep : k;  // forced entries 0..f-1
+  const int kp = k - f;               // still to choose among indices f..n-1
+
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sh_prefix, sh_krem;
+  __shared__ uint32_t wtot[2][kSelWaves][2];
+
+  for (int t = tid; t < budget; t += kSelThreads) {
+    if (t < f) out[t] = t;
+    else if (t >= k) out[t] = -1;
+  }
+  if (tid == 0) (kind ? a.s_cnt : a.v_cnt)[h] = k;
+  if (kp == 0) return;
+
+  // ---- radix select: threshold key T = kp-th largest key among candidates ------------------
+  uint32_t prefix = 0, krem = (uint32_t)kp;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int64_t i = f + tid; i < n; i += kSelThreads) {
+      const uint32_t key = order_key(sc[i]);
+      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t cum = 0;
+      int b = 255;
+      for (; b > 0; --b) {
+        const uint32_t c = hist[b];
+        if (cum + c >= krem) break;
+        cum += c;
+      }
+      sh_prefix = prefix | ((uint32_t)b << shift);
+      sh_krem = krem - cum;
+    }
+    __syncthreads();
+    prefix = sh_prefix;
+    krem = sh_krem;
+  }
+  const uint32_t T = prefix;
+  const uint32_t need_eq = krem;  // >= 1
+
+  // ---- ordered compaction -------------------------------------------------------------------
+  uint32_t run_gt = 0, run_eq = 0;  // totals over the chunks already done
+  const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  int par = 0;
+  for (int64_t base = f; base < n; base += (int64_t)kSelThreads * kSelItems, par ^= 1) {
+    uint64_t bg[kSelItems], be[kSelItems];
+    uint32_t tg = 0, te = 0;
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e) {
+      const int64_t i = base + (int64_t)wv * (64 * kSelItems) + e * 64 + lane;
+      uint32_t key = 0;
+      if (i < n) key = order_key(sc[i]);
+      bg[e] = __ballot(i < n && key > T);
+      be[e] = __ballot(i < n && key == T);
+      tg += __popcll(bg[e]);
+      te += __popcll(be[e]);
+    }
+    if (lane == 0) { wtot[par][wv][0] = tg; wtot[par][wv][1] = te; }
+    __syncthreads();
+    uint32_t gt_before = run_gt, eq_before = run_eq, cg = 0, ce = 0;
+    for (int w = 0; w < kSelWaves; ++w) {
+      const uint32_t g_ = wtot[par][w][0], e_ = wtot[par][w][1];
+      if (w < wv) { gt_before += g_; eq_before += e_; }
+      cg += g_; ce += e_;
+    }
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e) {
+      const int64_t i = base + (int64_t)wv * (64 * kSelItems) + e * 64 + lane;
+      const uint32_t gr = gt_before + __popcll(bg[e] & lt_mask);
+      const uint32_t er = eq_before + __popcll(be[e] & lt_mask);
+      const bool is_g = (bg[e] >> lane) & 1ull, is_e = (be[e] >> lane) & 1ull;
+      if (is_g) out[f + gr + (er < need_eq ? er : need_eq)] = (int32_t)i;
+      else if (is_e && er < need_eq) out[f + gr + er] = (int32_t)i;
+      gt_before += __popcll(bg[e]);
+      eq_before += __popcll(be[e]);
+    }
+    run_gt += cg;
+    run_eq += ce;
+    if (run_gt + (run_eq < need_eq ? run_eq : need_eq) >= (uint32_t)kp) break;
+  }
+}
+
+size_t select_ws_bytes(const vs_params&) { return 0; }
+
+hipError_t launch_select(const vs_params& p, const float* vscore, const float* sscore,
+                         int32_t* v_idx, int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void*,
+                         hipStream_t st) {
+  SelArgs a;
+  a.vscore = vscore; a.sscore = sscore; a.n = p.q_start + p.q_len;
+  a.v_budget = p.vertical_budget; a.s_budget = p.slash_budget;
+  a.keep_v = p.keep_first_cols; a.keep_s = p.keep_local_band;
+  a.v_idx = v_idx; a.v_cnt = v_cnt; a.s_idx = s_idx; a.s_cnt = s_cnt;
+  hipLaunchKernelGGL(k_select, dim3(p.n_q_heads, 2), dim3(kSelThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace vs

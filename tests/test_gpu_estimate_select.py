@@ -1,0 +1,76 @@
+"""GPU parity of estimation and selection against the fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2501_15383_amd as vs
+import vsgen
+from gpu_util import check_index_sets, chunk_of, dev, f64
+from helpers import rand_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,s,w", [
+    (4, 1, 64, 1024, 3072, 64),    # small configuration, last chunk
+    (4, 1, 64, 1024, 0, 64),       # first chunk
+    (7, 1, 128, 300, 2048, 64),    # GQA 7, ragged n_k, several key ranges
+    (5, 1, 128, 40, 0, 64),        # chunk shorter than the window
+    (8, 2, 128, 128, 1152, 16),    # short window
+    (3, 3, 64, 100, 64, 64),       # MHA
+])
+def test_estimate_matches_oracle(hq, hkv, d, c, s, w):
+    rng = np.random.default_rng(400 + c)
+    n_k = s + c
+    q = rand_bf16(rng, (c, hq, d)); k = rand_bf16(rng, (n_k, hkv, d))
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d), last_q=w)
+    rvs, rss, rlse = oracle.estimate(pb, q, k)
+    vsc, ssc, lse = vs.estimate(chunk_of(pb), dev(q), dev(k), want_lse=True)
+    torch.cuda.synchronize()
+    wp = min(w, c)
+    np.testing.assert_allclose(f64(lse), rlse, atol=2e-4, rtol=0)
+    # fp32 accumulation of bf16 products; sums of <= 64 probabilities
+    np.testing.assert_allclose(f64(vsc), rvs, rtol=2e-4, atol=1e-7)
+    np.testing.assert_allclose(f64(ssc), rss, rtol=2e-4, atol=1e-7)
+    np.testing.assert_allclose(f64(vsc).sum(1), wp, rtol=1e-4)
+    np.testing.assert_allclose(f64(ssc).sum(1), wp, rtol=1e-4)
+    # run-to-run identical
+    vsc2, ssc2, _ = vs.estimate(chunk_of(pb), dev(q), dev(k))
+    torch.cuda.synchronize()
+    assert torch.equal(vsc, vsc2) and torch.equal(ssc, ssc2)
+
+
+@pytest.mark.parametrize("n,bv,bs,kf,kb,hq", [(4096, 128, 256, 1, 64, 4), (1000, 37, 90, 0, 0, 3), (70000, 1000, 6096, 1, 64, 2),
+                                              (50, 128, 256, 1, 64, 2), (9000, 9000, 1, 3, 5, 2)])
+def test_select_is_exact_on_given_scores(n, bv, bs, kf, kb, hq):
+    # same fp32 scores on both sides: the kept sets must be identical, ties to the lower index
+    rng = np.random.default_rng(500 + n)
+    vsc = rng.random((hq, n)).astype(np.float32) ** 4
+    ssc = rng.random((hq, n)).astype(np.float32) ** 4
+    vsc[:, ::7] = vsc[:, 3:4]          # many exact ties
+    ssc[0, :] = 0.25                   # all equal
+    q_start = (n - 1) // 64 * 64            # q_start must be a multiple of the block; n_k = n
+    pb = oracle.Problem(hq, 1, 64, n - q_start, q_start, 1.0, vertical_budget=bv, slash_budget=bs,
+                        keep_first_cols=kf, keep_local_band=kb)
+    ref = oracle.select(pb, vsc.astype(np.float64), ssc.astype(np.float64))
+    got = vs.select(chunk_of(pb), torch.from_numpy(vsc).cuda(), torch.from_numpy(ssc).cuda())
+    torch.cuda.synchronize()
+    for r, g, nm in zip(ref, got, ["v_idx", "v_cnt", "s_idx", "s_cnt"]):
+        np.testing.assert_array_equal(g.cpu().numpy(), r, err_msg=nm)
+
+
+def test_estimate_then_select_on_small_configuration():
+    w = vsgen.WORKLOADS["tiny_4k"]
+    K, V = vsgen.make_kv(w); Q = vsgen.make_q(w, 0, w.n_ctx)
+    for ci in range(w.n_chunks):
+        s = ci * w.chunk
+        pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, s, w.softmax_scale,
+                            vertical_budget=w.vertical_budget, slash_budget=w.slash_budget)
+        rvs, rss, _ = oracle.estimate(pb, vsgen.as_u16(Q[s:s + w.chunk]), vsgen.as_u16(K))
+        ck = chunk_of(pb)
+        vsc, ssc, _ = vs.estimate(ck, Q[s:s + w.chunk].cuda(), K.cuda())
+        v_idx, v_cnt, s_idx, s_cnt = [x.cpu().numpy() for x in vs.select(ck, vsc, ssc)]
+        for h in range(w.n_q_heads):
+            check_index_sets(rvs[h], v_idx[h], v_cnt[h], w.vertical_budget, 1, f"chunk {ci} head {h} vertical")
+            check_index_sets(rss[h], s_idx[h], s_cnt[h], w.slash_budget, 64, f"chunk {ci} head {h} slash")
