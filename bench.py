@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the vertical-slash sparse prefill path on one MI355X.
+
+A step = one 32,768-token query chunk through the whole hot path
+(vs_estimate -> vs_select -> vs_sparse_attn_prefill) with the K/V cache already resident in
+HBM; the default workload is the LAST chunk of a 1,048,576-token context at the Qwen2.5-7B
+attention shape (28 query / 4 KV heads, head_dim 128), i.e. n_k = 1M keys visible.  The
+dense-causal kernel is timed on the same chunk for the speedup, and the fp64 CPU oracle is
+timed on a bounded sample of the same chunk.  One JSON line is printed.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b_1m] [--chunk-index -1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def cpu_baseline(w, pb_kwargs, Q, K, V, sets_host, target_s):
+    """Time the fp64 oracle on a bounded sample of this chunk and extrapolate to the chunk."""
+    import numpy as np
+
+    import oracle
+    import vsgen
+    pb = oracle.Problem(**pb_kwargs)
+    qh, kh, vh = vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V)
+    cores = oracle.num_threads()
+    t0 = time.time()
+    vs_, ss_, _ = oracle.estimate(pb, qh, kh, heads=[0])
+    t_est = time.time() - t0
+    t0 = time.time()
+    oracle.select_one(vs_[0], pb.vertical_budget, pb.keep_first_cols)
+    oracle.select_one(ss_[0], pb.slash_budget, pb.keep_local_band)
+    t_sel = time.time() - t0
+    # attention rows: spread over the chunk, sized from a 2-row probe to fill the time budget
+    rng = np.random.default_rng(7)
+    t0 = time.time()
+    oracle.sparse_attention(pb, qh, kh, vh, *sets_host, heads=[0], rows=[0, pb.q_len - 1])
+    t_probe = max(time.time() - t0, 1e-3)
+    budget = max(target_s - t_est - t_sel - t_probe, 1.0)
+    # two rows ran side by side, so one row costs about t_probe on one core
+    n_rows = int(min(pb.q_len, cores * max(1, int(budget / t_probe))))
+    rows = np.sort(rng.choice(pb.q_len, n_rows, replace=False))
+    t0 = time.time()
+    oracle.sparse_attention(pb, qh, kh, vh, *sets_host, heads=[0], rows=rows)
+    t_att = time.time() - t0
+    hq = pb.n_q_heads
+    chunk_s = hq * (t_est + t_sel) + t_att * (hq * pb.q_len) / n_rows
+    return {
+        "value": chunk_s * 1e3, "unit": "ms per 32K chunk (extrapolated from the sample)",
+        "cores": cores, "kind": "oracle",
+        "sample": (f"head 0 of {hq}: estimate ({t_est:.2f}s) + select ({t_sel:.2f}s) for the whole head, "
+                   f"masked attention for {n_rows} of {pb.q_len} rows ({t_att:.2f}s); "
+                   f"scaled by heads and rows to one chunk"),
+        "sample_seconds": t_est + t_sel + t_probe + t_att,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="7b_1m")
+    ap.add_argument("--chunk-index", type=int, default=-1, help="which chunk of the context (-1 = last)")
+    ap.add_argument("--n-ctx", type=int, default=0, help="override the context length (tokens)")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by KV head with no exchange inside "
+              "attention; multi-GPU figures are not produced). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2501_15383_amd as vs
+    import vsgen
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    vs.lib()   # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    w = vsgen.WORKLOADS[args.workload]
+    if args.n_ctx:
+        w = vsgen.scaled(w, n_ctx=args.n_ctx)
+    ci = args.chunk_index % w.n_chunks
+    s = ci * w.chunk
+    C = min(w.chunk, w.n_ctx - s)
+    n_k = s + C
+
+    t0 = time.time()
+    K, V = vsgen.make_kv(w, n_k, device=dev)
+    Q = vsgen.make_q(w, s, s + C, device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t0
+
+    bv = w.vertical_budget if not w.dense else 1
+    bs = w.slash_budget if not w.dense else 1
+    ck = vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, last_q=w.last_q,
+                  vertical_budget=bv, slash_budget=bs, keep_first_cols=w.keep_first_cols,
+                  keep_local_band=w.keep_local_band)
+    out = torch.empty((C, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+    vscore = torch.empty((w.n_q_heads, n_k), dtype=torch.float32, device=dev)
+    sscore = torch.empty_like(vscore)
+    sets = vs.alloc_index_sets(ck, dev)
+    ws_e = torch.empty(max(vs.workspace_bytes(ck, vs.VS_WS_ESTIMATE), 256), dtype=torch.uint8, device=dev)
+    ws_a = torch.empty(max(vs.workspace_bytes(ck, vs.VS_WS_SPARSE), 256), dtype=torch.uint8, device=dev)
+
+    def step(ev=None):
+        # the three stages of vs_prefill_chunk, called one by one on the same stream so that
+        # HIP events between them give the per-kernel times
+        if ev: ev[0].record()
+        if w.dense:
+            vs.dense_causal_prefill(ck, Q, K, V, out=out, ws=ws_a)
+            if ev: ev[1].record(); ev[2].record(); ev[3].record()
+            return
+        vs.estimate(ck, Q, K, vscore=vscore, sscore=sscore, ws=ws_e)
+        if ev: ev[1].record()
+        vs.select(ck, vscore, sscore, sets=sets)
+        if ev: ev[2].record()
+        vs.sparse_attn_prefill(ck, Q, K, V, *sets, out=out, ws=ws_a)
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [_events(4) for _ in range(args.steps)]
+    t0 = time.time()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.time() - t0) * 1e3 / args.steps
+    est_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    sel_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    att_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    if w.dense:
+        att_ms, est_ms, sel_ms = est_ms, 0.0, 0.0
+    gpu_ms = est_ms + sel_ms + att_ms
+
+    # ---- work accounting: issued 64x64 tiles -> FLOPs ---------------------------------------
+    tile_flops = 4.0 * w.head_dim * 64 * 64
+    n_qb = (C + 63) // 64
+    mb0 = s // 64
+    dense_tiles = w.n_q_heads * sum(mb0 + qb + 1 for qb in range(n_qb))
+    if w.dense:
+        issued = dense_tiles
+        slash_tiles = vert_tiles = 0
+    else:
+        tiles = vs.count_tiles(ck, *sets).cpu()
+        slash_tiles, vert_tiles = int(tiles[:, 0].sum()), int(tiles[:, 1].sum())
+        issued = slash_tiles + vert_tiles
+    att_tflops = issued * tile_flops / (att_ms * 1e-3) / 1e12
+
+    # ---- dense-causal kernel on the same chunk ----------------------------------------------
+    dense_ms = None
+    if not args.no_dense and not w.dense:
+        ws_d = torch.empty(max(vs.workspace_bytes(ck, vs.VS_WS_DENSE), 256), dtype=torch.uint8, device=dev)
+        out_d = torch.empty_like(out)
+        vs.dense_causal_prefill(ck, Q, K, V, out=out_d, ws=ws_d)
+        torch.cuda.synchronize()
+        e = _events(2)
+        e[0].record()
+        for _ in range(2):
+            vs.dense_causal_prefill(ck, Q, K, V, out=out_d, ws=ws_d)
+        e[1].record()
+        torch.cuda.synchronize()
+        dense_ms = e[0].elapsed_time(e[1]) / 2
+        del out_d
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_k_attention_{w.name}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+
+    cpu = None
+    if not args.no_cpu:
+        pbk = dict(n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, q_len=C, q_start=s,
+                   softmax_scale=w.softmax_scale, last_q=w.last_q, vertical_budget=bv, slash_budget=bs,
+                   keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
+        if w.dense:
+            import numpy as np
+            allv = np.zeros((w.n_q_heads, 1), np.int32)
+            sets_h = (allv, np.ones(w.n_q_heads, np.int32), allv.copy(), np.ones(w.n_q_heads, np.int32))
+        else:
+            sets_h = tuple(x.cpu().numpy() for x in sets)
+        cpu = cpu_baseline(w, pbk, Q, K, V, sets_h, args.cpu_seconds)
+
+    res = {
+        "metric": "ms per 32K prefill chunk at 1M ctx (estimate + select + block-sparse attention)",
+        "value": gpu_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": gpu_ms, "wall_ms_per_step": wall_ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: chunk {ci} of {w.n_chunks} (q_start {s}, {C} rows, n_k {n_k}), "
+                               f"Hq {w.n_q_heads} / Hkv {w.n_kv_heads} / D {w.head_dim}, W {w.last_q}, "
+                               f"Bv {bv}, Bs {bs}", "input_gen_s": round(t_gen, 2)},
+        "phases_ms": {"estimate": est_ms, "select": sel_ms, "sparse_attention": att_ms},
+        "tiles": {"slash": slash_tiles, "vertical": vert_tiles, "dense_equivalent": dense_tiles,
+                  "computed_fraction": issued / dense_tiles},
+        "effective_tflops": att_tflops, "pct_bf16_mfma_peak": 100.0 * att_tflops / PEAK_BF16_TFLOPS,
+        "dense_ms": dense_ms,
+        "dense_tflops": (dense_tiles * tile_flops / (dense_ms * 1e-3) / 1e12) if dense_ms else None,
+        "speedup_vs_dense": (dense_ms / gpu_ms) if dense_ms else None,
+        "roofline": {"kernel": "k_attention", "bound": "mfma", "achieved": att_tflops, "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": att_tflops / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "flops_per_launch": issued * tile_flops, "avg_launch_ms": att_ms},
+        "estimate_hbm_gbs": None if w.dense else (2.0 * n_k * w.n_kv_heads * w.head_dim * 2 + 2.0 * w.n_q_heads * n_k * 4)
+        / (est_ms * 1e-3) / 1e9,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

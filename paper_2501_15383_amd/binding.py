@@ -147,31 +147,44 @@ def _chk_inner(t, name, d):
     assert t.dtype == torch.bfloat16 and t.dim() == 3 and t.stride(2) == 1 and t.shape[2] == d, name
 
 
-def estimate(ck: Chunk, q, k, want_lse=False):
+def estimate(ck: Chunk, q, k, want_lse=False, vscore=None, sscore=None, ws=None):
     """vs_estimate.  q: bf16 [C][Hq][D] (the chunk), k: bf16 [>=n_k][Hkv][D].
-    Returns vscore, sscore (fp32 [Hq][n_k]) and lse_lastq (fp32 [Hq][W'] or None)."""
+    Returns vscore, sscore (fp32 [Hq][n_k]) and lse_lastq (fp32 [Hq][W'] or None).
+    vscore / sscore / ws may be passed in to avoid allocating."""
     _chk_inner(q, "q", ck.head_dim); _chk_inner(k, "k", ck.head_dim)
     assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k
     dev = q.device
-    vscore = torch.empty((ck.n_q_heads, ck.n_k), dtype=torch.float32, device=dev)
-    sscore = torch.empty_like(vscore)
+    if vscore is None:
+        vscore = torch.empty((ck.n_q_heads, ck.n_k), dtype=torch.float32, device=dev)
+    if sscore is None:
+        sscore = torch.empty((ck.n_q_heads, ck.n_k), dtype=torch.float32, device=dev)
+    for t in (vscore, sscore):
+        assert t.dtype == torch.float32 and t.is_contiguous() and t.shape == (ck.n_q_heads, ck.n_k)
     lse = torch.empty((ck.n_q_heads, min(ck.last_q, ck.q_len)), dtype=torch.float32, device=dev) if want_lse else None
-    ws, n = _ws(ck, VS_WS_ESTIMATE, dev)
+    if ws is None:
+        ws = torch.empty(max(workspace_bytes(ck, VS_WS_ESTIMATE), 256), dtype=torch.uint8, device=dev)
     p = ck.params(q=q, k=k)
     _check(lib().vs_estimate(C.byref(p), _ptr(q), _ptr(k), _ptr(vscore), _ptr(sscore), _ptr(lse),
-                             _ptr(ws), n, _stream()), "vs_estimate")
+                             _ptr(ws), ws.numel(), _stream()), "vs_estimate")
     return vscore, sscore, lse
 
 
-def select(ck: Chunk, vscore, sscore):
-    """vs_select.  Returns v_idx [Hq][Bv], v_cnt [Hq], s_idx [Hq][Bs], s_cnt [Hq] (int32)."""
+def alloc_index_sets(ck: Chunk, device):
+    """Uninitialised v_idx [Hq][Bv], v_cnt [Hq], s_idx [Hq][Bs], s_cnt [Hq] (int32)."""
+    return (torch.empty((ck.n_q_heads, ck.vertical_budget), dtype=torch.int32, device=device),
+            torch.empty(ck.n_q_heads, dtype=torch.int32, device=device),
+            torch.empty((ck.n_q_heads, ck.slash_budget), dtype=torch.int32, device=device),
+            torch.empty(ck.n_q_heads, dtype=torch.int32, device=device))
+
+
+def select(ck: Chunk, vscore, sscore, sets=None):
+    """vs_select.  Returns v_idx [Hq][Bv], v_cnt [Hq], s_idx [Hq][Bs], s_cnt [Hq] (int32);
+    `sets` (from alloc_index_sets) may be passed in to avoid allocating."""
     assert vscore.dtype == torch.float32 and vscore.is_contiguous() and vscore.shape == (ck.n_q_heads, ck.n_k)
     assert sscore.dtype == torch.float32 and sscore.is_contiguous() and sscore.shape == (ck.n_q_heads, ck.n_k)
     dev = vscore.device
-    v_idx = torch.empty((ck.n_q_heads, ck.vertical_budget), dtype=torch.int32, device=dev)
-    s_idx = torch.empty((ck.n_q_heads, ck.slash_budget), dtype=torch.int32, device=dev)
-    v_cnt = torch.empty(ck.n_q_heads, dtype=torch.int32, device=dev)
-    s_cnt = torch.empty(ck.n_q_heads, dtype=torch.int32, device=dev)
+    v_idx, v_cnt, s_idx, s_cnt = alloc_index_sets(ck, dev) if sets is None else sets
+    _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt)
     ws, n = _ws(ck, VS_WS_SELECT, dev)
     p = ck.params()
     _check(lib().vs_select(C.byref(p), _ptr(vscore), _ptr(sscore), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx),

@@ -65,22 +65,26 @@ __device__ __forceinline__ int bm_next(const uint32_t* bm, int from, int limit) 
   }
 }
 
+// LDS bytes of one workgroup: K and V tiles double-buffered + the gathered column indices.
+template <int D>
+constexpr int attn_lds_bytes() { return 2 * 64 * (D + 8) * 2 + 2 * 64 * (D + 32) * 2 + 2 * 64 * 4; }
+
 template <int D, int NQB>
 __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   constexpr int NT = 128 * NQB;        // threads
-  constexpr int KS = D + 8;            // LDS row stride of K tile [64][D], elements
-  constexpr int VS = 64 + 8;           // LDS row stride of V^T tile [D][64], elements
+  constexpr int KS = D + 8;            // LDS row stride of the K tile [64 keys][D], elements
+  constexpr int VR = D + 32;           // LDS row stride of the V tile [64 keys][D], elements
   constexpr int DCH = D / 8;           // 16-byte chunks per row
   constexpr int DSTEPS = D / 16;       // MFMA k-steps of QK^T
   constexpr int DB = D / 32;           // 32-row blocks of O^T
-  constexpr int KPT = 64 * DCH / NT;   // K chunks per thread
-  constexpr int VUNITS = 16 * DCH;     // (4 keys x 8 dims) register tiles of V
-  constexpr int VPT = (VUNITS + NT - 1) / NT;
-  static_assert(64 * DCH % NT == 0, "K tile must divide over the threads");
+  constexpr int CPT = 64 * DCH / NT;   // chunks per thread per tile, for K and for V
+  constexpr int KBUF = 64 * KS, VBUF = 64 * VR;
+  static_assert(64 * DCH % NT == 0, "tile must divide over the threads");
 
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[64 * KS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vt[D * VS];
-  __shared__ int32_t vidx_s[64];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  __bf16* const Ks = (__bf16*)smem_raw;                 // [2][KBUF]
+  __bf16* const Vs = Ks + 2 * KBUF;                     // [2][VBUF]
+  int32_t* const vidx_s = (int32_t*)(Vs + 2 * VBUF);    // [2][64]
 
   // ---- which (query tile, head) -------------------------------------------------------
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -129,7 +133,6 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 
   // ---- tile iterator (uniform over the workgroup) -----------------------------------------
   // kind 0: slash tile, idx = cc; kind 1: vertical tile, idx = vt; kind 2: end
-  int cur_kind = 0, cur_idx = -1;
   auto advance = [&](int& kind, int& idx) {
     if (kind == 0) {
       int cc = bm_next(bmU, idx + 1, cc_limit);
@@ -142,8 +145,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     }
     kind = 2; idx = 0;
   };
-
-  // key index that tile row r comes from
+  // key index that tile row r comes from (general path)
   auto src_row = [&](int kind, int idx, int r) -> int64_t {
     if (kind == 0) {
       int64_t j = (int64_t)(m0 - (idx - (NQB - 1))) * 64 + r;
@@ -153,64 +155,131 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     return pos < vcnt ? (int64_t)vidx_h[pos] : 0;
   };
 
-  u32x4 kst[KPT];
-  u32x4 vst[VPT][4];
+  // ---- staging: global -> registers -> LDS ------------------------------------------------
+  // chunk x = tid + e NT of a tile: row x / DCH, 16-byte chunk x % DCH
+  uint32_t koff[CPT], voff[CPT];  // byte offsets inside a contiguous 64-key block
+#pragma unroll
+  for (int e = 0; e < CPT; ++e) {
+    const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
+    koff[e] = (uint32_t)(r * a.k_stride_tok * 2 + ch * 16);
+    voff[e] = (uint32_t)(r * a.v_stride_tok * 2 + ch * 16);
+  }
+  u32x4 kst[CPT], vst[CPT];
   int32_t my_vidx = 0;
   auto load_tile = [&](int kind, int idx) {
+    if (kind == 0) {
+      const int64_t j0 = (int64_t)(m0 - (idx - (NQB - 1))) * 64;
+      if (j0 + 64 <= n_k) {  // whole block in range: one uniform base + per-thread 32-bit offsets
+        const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
+        const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
 #pragma unroll
-    for (int e = 0; e < KPT; ++e) {
-      const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
-      kst[e] = *(const u32x4*)(kbase + src_row(kind, idx, r) * a.k_stride_tok + ch * 8);
+        for (int e = 0; e < CPT; ++e) kst[e] = *(const u32x4*)(kt + koff[e]);
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) vst[e] = *(const u32x4*)(vt + voff[e]);
+        return;
+      }
     }
 #pragma unroll
-    for (int e = 0; e < VPT; ++e) {
-      const int x = tid + e * NT;
-      if (x < VUNITS) {
-        const int jq = x & 15, ch = x >> 4;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
-          vst[e][rr] = *(const u32x4*)(vbase + src_row(kind, idx, 4 * jq + rr) * a.v_stride_tok + ch * 8);
-      }
+    for (int e = 0; e < CPT; ++e) {
+      const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
+      const int64_t j = src_row(kind, idx, r);
+      kst[e] = *(const u32x4*)(kbase + j * a.k_stride_tok + ch * 8);
+      vst[e] = *(const u32x4*)(vbase + j * a.v_stride_tok + ch * 8);
     }
     if (kind == 1 && tid < 64) my_vidx = (int32_t)src_row(kind, idx, tid);
   };
-  auto store_tile = [&](int kind) {
+  auto store_tile = [&](int buf, int kind) {
 #pragma unroll
-    for (int e = 0; e < KPT; ++e) {
+    for (int e = 0; e < CPT; ++e) {
       const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
-      *(u32x4*)&Ks[r * KS + ch * 8] = kst[e];
+      *(u32x4*)&Ks[buf * KBUF + r * KS + ch * 8] = kst[e];
+      *(u32x4*)&Vs[buf * VBUF + r * VR + ch * 8] = vst[e];
     }
-#pragma unroll
-    for (int e = 0; e < VPT; ++e) {
-      const int x = tid + e * NT;
-      if (x < VUNITS) {
-        const int jq = x & 15, ch = x >> 4;
-        // key quad jq = [jb t u h] is stored at slot quad [jb t h u]: a lane's 8 PV keys are contiguous
-        const int sq = (jq & 12) | ((jq & 1) << 1) | ((jq >> 1) & 1);
-#pragma unroll
-        for (int e2 = 0; e2 < 8; ++e2) {
-          const int w = e2 >> 1;
-          const uint32_t sel = (e2 & 1) ? 0x07060302u : 0x05040100u;
-          u32x2 pk;
-          pk[0] = __builtin_amdgcn_perm(vst[e][1][w], vst[e][0][w], sel);
-          pk[1] = __builtin_amdgcn_perm(vst[e][3][w], vst[e][2][w], sel);
-          *(u32x2*)&Vt[(ch * 8 + e2) * VS + 4 * sq] = pk;
-        }
-      }
-    }
-    if (kind == 1 && tid < 64) vidx_s[tid] = my_vidx;
+    if (kind == 1 && tid < 64) vidx_s[buf * 64 + tid] = my_vidx;
   };
 
-  advance(cur_kind, cur_idx);
-  if (cur_kind != 2) load_tile(cur_kind, cur_idx);
+  // per-lane LDS element offsets of the MFMA operands
+  const int k_lane = (lane & 31) * KS + 8 * hh;  // K rows as A operand of S^T = K Q^T
+  // V^T operand through the transposing LDS read: inside each 16-lane group, lane L supplies
+  // the address of V[J0 + L/4][D0 + 4 (L%4) .. +3] and receives V[J0 .. J0+3][D0 + L]
+  const int v_lane = (((lane & 15) >> 2) + 4 * hh) * VR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-  while (cur_kind != 2) {
-    store_tile(cur_kind);
-    __syncthreads();
-    int nxt_kind = cur_kind, nxt_idx = cur_idx;
+  auto qk_step = [&](f32x16& acc, const __bf16* kb, int jb, int st) {
+    const bf16x8 ka = *(const bf16x8*)&kb[k_lane + 32 * jb * KS + 16 * st];
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[st], acc, 0, 0, 0);
+  };
+  // keys of MFMA k-slots 8 hh + 0..7 in step tt of key block jb: 32 jb + 16 tt + 8 (e/4) + 4 hh + e%4
+  auto pv_step = [&](const __bf16* vb, const bf16x8 pb, int jb, int tt, int db) {
+    typedef bf16x4 __attribute__((address_space(3))) * lds_b4;
+    const __bf16* p0 = &vb[v_lane + (32 * jb + 16 * tt) * VR + 32 * db];
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0 + 8 * VR));
+    const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[db], 0, 0, 0);
+  };
+  auto to_bf16 = [&](const f32x16& sv, int tt) -> bf16x8 {
+    f32x8 pf;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) pf[x] = sv[8 * tt + x];
+    return __builtin_convertvector(pf, bf16x8);
+  };
+  // running-max update with the maximum of a block of scores (base-2 domain).  When some row's
+  // maximum grows, everything already expressed relative to the old maximum is rescaled: the
+  // row sum, O, and `pend` (probabilities computed but not yet multiplied into O) if has_pend.
+  auto update_max_impl = [&](float mx, f32x16& pend, const bool has_pend) -> float {
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx * a.scale_log2);
+    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+    m_run = m_new;
+    if (__any(alpha != 1.0f)) {
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
+      if (has_pend) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) pend[x] *= alpha;
+      }
+    }
+    return m_use;
+  };
+  auto block_max = [&](const f32x16& sv) -> float {
+    float mx = sv[0];
+#pragma unroll
+    for (int x = 1; x < 16; ++x) mx = fmaxf(mx, sv[x]);
+    return mx;
+  };
+  auto exp_block = [&](f32x16& sv, float m_use) {
+    float ps = 0.f;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], a.scale_log2, -m_use));
+      sv[x] = p;
+      ps += p;
+    }
+    l_run += ps;
+  };
+
+  // ---- prologue: tile 0 -> LDS buffer 0, tile 1 -> registers ---------------------------------
+  int cur_kind = 0, cur_idx = -1;
+  advance(cur_kind, cur_idx);
+  if (cur_kind != 2) {
+    load_tile(cur_kind, cur_idx);
+    store_tile(0, cur_kind);
+  }
+  int nxt_kind = cur_kind, nxt_idx = cur_idx;
+  if (cur_kind != 2) {
     advance(nxt_kind, nxt_idx);
     if (nxt_kind != 2) load_tile(nxt_kind, nxt_idx);
+  }
+  __syncthreads();
+  int buf = 0;
 
+  while (cur_kind != 2) {
+    const __bf16* kb = Ks + buf * KBUF;
+    const __bf16* vb = Vs + buf * VBUF;
     // ---- does this wave take part, and with which element mask? ----------------------
     bool part = wave_valid;
     bool diag = false;            // slash tile on the query block's own diagonal
@@ -222,100 +291,106 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       diag = ad == 0;
     } else {
       const int pos = 64 * cur_idx + lane;
-      const int j = vidx_s[lane];
+      const int j = vidx_s[buf * 64 + lane];
       const int ad = (m0 + t) - (j >> 6);
       const bool ok = pos < vcnt && ad >= 0 && !bm_test(bmA, ad);
       vmask = __ballot(ok);
       dmask = __ballot(ok && ad == 0);
       part = part && vmask != 0;
     }
+    const bool masked = diag || cur_kind == 1;
 
+    f32x16 s[2];
     if (part) {
-      // ---- S^T = K Q^T : two 32-key blocks --------------------------------------------
-      f32x16 s[2];
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb) {
+      for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
         for (int x = 0; x < 16; ++x) s[jb][x] = 0.f;
+      if (!masked) {
+        // -------- fast path: the two 32-key halves are software-pipelined --------------
+        // S0; first half of S1 ahead of the max of S0; exp(S0) under the rest of S1;
+        // PV(0) under exp(S1); PV(1) after the staging below.
 #pragma unroll
-        for (int st = 0; st < DSTEPS; ++st) {
-          const bf16x8 ka = *(const bf16x8*)&Ks[(32 * jb + (lane & 31)) * KS + 16 * st + 8 * hh];
-          s[jb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[st], s[jb], 0, 0, 0);
+        for (int st = 0; st < DSTEPS; ++st) qk_step(s[0], kb, 0, st);
+#pragma unroll
+        for (int st = 0; st < DSTEPS / 2; ++st) qk_step(s[1], kb, 1, st);
+        const float mu0 = update_max_impl(block_max(s[0]), s[0], false);
+#pragma unroll
+        for (int st = DSTEPS / 2; st < DSTEPS; ++st) qk_step(s[1], kb, 1, st);
+        exp_block(s[0], mu0);
+        // P0 is relative to the old maximum: if S1 raises it, P0 is rescaled with O before PV(0)
+        const float mu1 = update_max_impl(block_max(s[1]), s[0], true);
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const bf16x8 pb = to_bf16(s[0], tt);
+#pragma unroll
+          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
         }
-      }
-      // element x of block jb is key r = 32 jb + 8 (x/4) + 4 hh + (x%4) of the tile
-      if (diag) {
+        exp_block(s[1], mu1);
+      } else {
+        // -------- masked tile (own diagonal block, or gathered columns): plain order ------
 #pragma unroll
         for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-            if (r > il) s[jb][x] = -INFINITY;
-          }
-      } else if (cur_kind == 1) {
+          for (int st = 0; st < DSTEPS; ++st) qk_step(s[jb], kb, jb, st);
+        // element x of block jb is key r = 32 jb + 8 (x/4) + 4 hh + (x%4) of the tile
+        if (diag) {
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb) {
-          const uint32_t vb = (uint32_t)(vmask >> (32 * jb + 4 * hh));
-          const uint32_t db_ = (uint32_t)(dmask >> (32 * jb + 4 * hh));
+          for (int jb = 0; jb < 2; ++jb)
 #pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            const int bit = 8 * (x >> 2) + (x & 3);
-            bool ok = (vb >> bit) & 1u;
-            if (dmask != 0 && ((db_ >> bit) & 1u)) {
+            for (int x = 0; x < 16; ++x) {
               const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-              ok = ok && (vidx_s[r] & 63) <= il;
+              if (r > il) s[jb][x] = -INFINITY;
             }
-            if (!ok) s[jb][x] = -INFINITY;
+        } else {
+#pragma unroll
+          for (int jb = 0; jb < 2; ++jb) {
+            const uint32_t vb_ = (uint32_t)(vmask >> (32 * jb + 4 * hh));
+            const uint32_t db_ = (uint32_t)(dmask >> (32 * jb + 4 * hh));
+#pragma unroll
+            for (int x = 0; x < 16; ++x) {
+              const int bit = 8 * (x >> 2) + (x & 3);
+              bool ok = (vb_ >> bit) & 1u;
+              if (dmask != 0 && ((db_ >> bit) & 1u)) {
+                const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
+                ok = ok && (vidx_s[buf * 64 + r] & 63) <= il;
+              }
+              if (!ok) s[jb][x] = -INFINITY;
+            }
           }
         }
-      }
-      // ---- online softmax (base 2) ----------------------------------------------------
-      float mx = s[0][0];
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) mx = fmaxf(mx, s[jb][x]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx * a.scale_log2);
-      const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      m_run = m_new;
-      l_run *= alpha;
-      if (__any(alpha != 1.0f)) {
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
-      }
-      float psum = 0.f;
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[jb][x], a.scale_log2, -m_use));
-          s[jb][x] = p;
-          psum += p;
-        }
-      l_run += psum;
-      // ---- O^T += V^T P^T ----------------------------------------------------------------
-#pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
+        const float mu = update_max_impl(fmaxf(block_max(s[0]), block_max(s[1])), s[0], false);
+        exp_block(s[0], mu);
+        exp_block(s[1], mu);
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt) {
-          f32x8 pf;
+          const bf16x8 pb = to_bf16(s[0], tt);
 #pragma unroll
-          for (int x = 0; x < 8; ++x) pf[x] = s[jb][8 * tt + x];
-          const bf16x8 pb = __builtin_convertvector(pf, bf16x8);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const bf16x8 va = *(const bf16x8*)&Vt[(32 * db + (lane & 31)) * VS + 32 * jb + 16 * tt + 8 * hh];
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[db], 0, 0, 0);
-          }
+          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
         }
+      }
+    }
+
+    // ---- staging: next tile registers -> other LDS buffer; tile after next -> registers ----
+    int nn_kind = nxt_kind, nn_idx = nxt_idx;
+    if (nxt_kind != 2) {
+      store_tile(buf ^ 1, nxt_kind);
+      advance(nn_kind, nn_idx);
+      if (nn_kind != 2) load_tile(nn_kind, nn_idx);
+    }
+
+    if (part) {
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 pb = to_bf16(s[1], tt);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) pv_step(vb, pb, 1, tt, db);
+      }
     }
     __syncthreads();
-    cur_kind = nxt_kind;
-    cur_idx = nxt_idx;
+    cur_kind = nxt_kind; cur_idx = nxt_idx;
+    nxt_kind = nn_kind; nxt_idx = nn_idx;
+    buf ^= 1;
   }
 
   // ---- normalise and store ------------------------------------------------------------------
@@ -455,10 +530,23 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
   a.scale_log2 = p.softmax_scale * kLog2e;
   const int64_t groups = (int64_t)a.n_qtiles * p.n_kv_heads;
   const int64_t blocks = ceil_div(groups, 8) * 8 * a.group;
+  // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention<128, NQB>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes<128>());
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention<64, NQB>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes<64>());
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   if (p.head_dim == 128)
-    hipLaunchKernelGGL((k_attention<128, NQB>), dim3((unsigned)blocks), dim3(128 * NQB), 0, st, a);
+    hipLaunchKernelGGL((k_attention<128, NQB>), dim3((unsigned)blocks), dim3(128 * NQB),
+                       attn_lds_bytes<128>(), st, a);
   else
-    hipLaunchKernelGGL((k_attention<64, NQB>), dim3((unsigned)blocks), dim3(128 * NQB), 0, st, a);
+    hipLaunchKernelGGL((k_attention<64, NQB>), dim3((unsigned)blocks), dim3(128 * NQB),
+                       attn_lds_bytes<64>(), st, a);
   return hipGetLastError();
 }
 
