@@ -43,12 +43,7 @@ int check_ws(const void* ws, size_t have, size_t need) {
   return VS_OK;
 }
 
-size_t bitmaps_bytes(const vs_params& p, bool dense) {
-  const size_t heads = dense ? 1 : (size_t)p.n_q_heads;
-  return align_up(heads * (size_t)bitmap_words(p.q_start + p.q_len) * sizeof(uint32_t), 256);
-}
-
-size_t sparse_ws_bytes(const vs_params& p, bool dense) { return 2 * bitmaps_bytes(p, dense); }
+size_t sparse_ws_bytes(const vs_params& p, bool dense) { return blocklist_bytes(p, dense); }
 
 // layout of the VS_WS_CHUNK workspace
 struct ChunkWs {
@@ -142,12 +137,11 @@ int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, con
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
   if (rc != VS_OK) return rc;
-  uint32_t* bm_a = (uint32_t*)ws;
-  uint32_t* bm_u = (uint32_t*)((char*)ws + bitmaps_bytes(*p, false));
+  const BlockList bl = blocklist_layout(*p, false, ws);
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = launch_build_bitmaps(*p, s_idx, s_cnt, false, bm_a, bm_u, st);
+  hipError_t e = launch_build_blocklist(*p, s_idx, s_cnt, false, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, k, v, v_idx, v_cnt, false, bm_a, bm_u, out, lse, st));
+  return hip_status(launch_attention(*p, q, k, v, v_idx, v_cnt, false, bl, out, lse, st));
 }
 
 int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, const void* v,
@@ -158,12 +152,11 @@ int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, co
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, true));
   if (rc != VS_OK) return rc;
-  uint32_t* bm_a = (uint32_t*)ws;
-  uint32_t* bm_u = (uint32_t*)((char*)ws + bitmaps_bytes(*p, true));
+  const BlockList bl = blocklist_layout(*p, true, ws);
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = launch_build_bitmaps(*p, nullptr, nullptr, true, bm_a, bm_u, st);
+  hipError_t e = launch_build_blocklist(*p, nullptr, nullptr, true, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, k, v, nullptr, nullptr, true, bm_a, bm_u, out, lse, st));
+  return hip_status(launch_attention(*p, q, k, v, nullptr, nullptr, true, bl, out, lse, st));
 }
 
 int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const void* v, void* out,
@@ -199,12 +192,11 @@ int vs_count_tiles(const vs_params* p, const int32_t* v_idx, const int32_t* v_cn
   if (!v_idx || !v_cnt || !s_idx || !s_cnt || !tiles) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
   if (rc != VS_OK) return rc;
-  uint32_t* bm_a = (uint32_t*)ws;
-  uint32_t* bm_u = (uint32_t*)((char*)ws + bitmaps_bytes(*p, false));
+  const BlockList bl = blocklist_layout(*p, false, ws);
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = launch_build_bitmaps(*p, s_idx, s_cnt, false, bm_a, bm_u, st);
+  hipError_t e = launch_build_blocklist(*p, s_idx, s_cnt, false, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_count_tiles(*p, v_idx, v_cnt, bm_a, tiles, st));
+  return hip_status(launch_count_tiles(*p, v_idx, v_cnt, bl, tiles, st));
 }
 
 }  // extern "C"

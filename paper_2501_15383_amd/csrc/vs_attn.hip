@@ -15,12 +15,17 @@
 //  * S^T = K Q^T with v_mfma_f32_32x32x16_bf16: the accumulator then holds, per lane, one
 //    query and 16 keys, so the row maximum / sum need one cross-lane step, and P^T is already
 //    the B operand of the second MFMA (O^T = V^T P^T) -- P never goes through LDS.
-//  * V is transposed while it is written to LDS (4x8 register tiles, v_perm) because the PV
-//    contraction runs over keys; key slots are permuted so that a lane's 8 keys are one
-//    16-byte LDS read.
-//  * global -> register prefetch of tile t+1 overlaps the MFMA work of tile t.
+//  * V stays row-major in LDS and is read with the transposing LDS load (ds_read_b64_tr_b16)
+//    as the A operand of the PV contraction, which runs over keys.
+//  * K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4, no staging
+//    registers), double-buffered: the copy of tile t+1 runs under the MFMA work of tile t,
+//    one barrier per tile.  Rows are unpadded; 16-byte chunks are XOR-swizzled instead.
+//  * inside a tile the two 32-key halves are software-pipelined (QK^T of the second half
+//    under the softmax of the first).
 //  * blockIdx -> (tile, head): the G heads that share a KV head and the same query tile run
 //    on one XCD back to back (shared L2), heaviest (latest) query tiles first.
+#include <stdlib.h>
+
 #include "vs_common.h"
 
 namespace vs {
@@ -33,9 +38,10 @@ struct AttnArgs {
   float* lse;
   int64_t q_stride_tok, q_stride_head, k_stride_tok, k_stride_head;
   int64_t v_stride_tok, v_stride_head, o_stride_tok, o_stride_head;
-  const uint32_t* bm_a;
-  const uint32_t* bm_u;
-  int64_t bm_stride;  // words per head, 0 = one bitmap shared by all heads (dense)
+  const uint32_t* bm_a;  // block-diagonal bitmap per head
+  const uint32_t* ent;   // key-block entry list per head (see BlockList)
+  int64_t bm_stride;     // words per head, 0 = one bitmap shared by all heads (dense)
+  int64_t ent_stride;    // entries per head, 0 = one list shared by all heads (dense)
   const int32_t* v_idx;  // null: no vertical phase
   const int32_t* v_cnt;
   int32_t v_budget;
@@ -43,48 +49,55 @@ struct AttnArgs {
   int32_t n_qtiles;
   int64_t q_len, q_start;
   float scale_log2;  // softmax_scale * log2(e)
+  int dbg;
 };
 
 __device__ __forceinline__ bool bm_test(const uint32_t* bm, int i) {
   return (bm[i >> 5] >> (i & 31)) & 1u;
 }
 
-// smallest set bit index >= from and < limit, else limit
-__device__ __forceinline__ int bm_next(const uint32_t* bm, int from, int limit) {
-  if (from >= limit) return limit;
-  int w = from >> 5;
-  uint32_t x = bm[w] & (~0u << (from & 31));
-  while (true) {
-    if (x) {
-      int r = (w << 5) + __builtin_ctz(x);
-      return r < limit ? r : limit;
-    }
-    ++w;
-    if ((w << 5) >= limit) return limit;
-    x = bm[w];
-  }
-}
-
-// LDS bytes of one workgroup: K and V tiles double-buffered + the gathered column indices.
+// LDS bytes of one workgroup: K and V tiles (unpadded, chunk-swizzled), double-buffered, the
+// gathered column indices of a vertical tile, and per-wave mask thresholds.
 template <int D>
-constexpr int attn_lds_bytes() { return 2 * 64 * (D + 8) * 2 + 2 * 64 * (D + 32) * 2 + 2 * 64 * 4; }
+constexpr int attn_lds_bytes() { return 4 * 64 * D * 2 + 2 * 64 * 4 + 8 * 64; }
+
+// Direct global -> LDS copy, 16 bytes per lane: lane L's bytes land at lds_addr + 16 L
+// (lds_addr is wave-uniform and goes through M0).  Completion is tracked by vmcnt.
+__device__ __forceinline__ void dma16_uniform_base(uint32_t lds_addr, const void* sbase, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma16_lane_ptr(uint32_t lds_addr, const void* ptr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(lds_addr), "v"(ptr) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)p;
+}
 
 template <int D, int NQB>
 __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
-  constexpr int NT = 128 * NQB;        // threads
-  constexpr int KS = D + 8;            // LDS row stride of the K tile [64 keys][D], elements
-  constexpr int VR = D + 32;           // LDS row stride of the V tile [64 keys][D], elements
   constexpr int DCH = D / 8;           // 16-byte chunks per row
   constexpr int DSTEPS = D / 16;       // MFMA k-steps of QK^T
   constexpr int DB = D / 32;           // 32-row blocks of O^T
-  constexpr int CPT = 64 * DCH / NT;   // chunks per thread per tile, for K and for V
-  constexpr int KBUF = 64 * KS, VBUF = 64 * VR;
-  static_assert(64 * DCH % NT == 0, "tile must divide over the threads");
+  constexpr int TILE = 64 * D;         // elements of one K or V tile in LDS (rows unpadded)
+  constexpr int RPG = 512 / D;         // rows in one 1 KiB group (= one wave-wide copy)
+  constexpr int NG = 64 / RPG;         // groups per tile
+  constexpr int GPW = NG / (2 * NQB);  // groups per wave
+  constexpr int R = 128 / D;           // rows per 256 bytes of LDS
+  static_assert(NG % (2 * NQB) == 0, "tile must divide over the waves");
+  // LDS layout.  Row r of a tile starts at r * D elements; its 16-byte chunk c is stored in
+  // slot c ^ f(r) for K and c ^ g(r) for V, which spreads the MFMA operand reads over all
+  // banks without padding (the copy engine writes 1 KiB contiguously per instruction):
+  //   f(r) = (r / R) % DCH                      16 consecutive keys of one d-chunk (K reads)
+  //   g(r) = (((r / R) & 3) << 2) & (DCH - 1)   4 keys x 4 d-chunks (transposing V reads)
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  __bf16* const Ks = (__bf16*)smem_raw;                 // [2][KBUF]
-  __bf16* const Vs = Ks + 2 * KBUF;                     // [2][VBUF]
-  int32_t* const vidx_s = (int32_t*)(Vs + 2 * VBUF);    // [2][64]
+  __bf16* const Ks = (__bf16*)smem_raw;               // [2][TILE]
+  __bf16* const Vs = Ks + 2 * TILE;                   // [2][TILE]
+  int32_t* const vidx_s = (int32_t*)(Vs + 2 * TILE);  // [2][64]
+  uint8_t* const need_s = (uint8_t*)(vidx_s + 2 * 64);  // [waves][64], private to each wave
+  const uint32_t ks_addr = lds_address(Ks), vs_addr = lds_address(Vs);
 
   // ---- which (query tile, head) -------------------------------------------------------
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -93,7 +106,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int qt = a.n_qtiles - 1 - gi / a.n_kv_heads;
   const int g = gi % a.n_kv_heads, h = g * a.group + hin;
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform
   const int t = wv >> 1;                          // query block of this wave inside the tile
   const int il = ((wv & 1) << 5) + (lane & 31);   // row inside the query block
   const int hh = lane >> 5;
@@ -106,9 +120,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int64_t last_pos = a.q_start + row0 + rows_in_tile - 1;
 
   const uint32_t* bmA = a.bm_a + (int64_t)h * a.bm_stride;
-  const uint32_t* bmU = a.bm_u + (int64_t)h * a.bm_stride;
+  const uint32_t* ent_h = a.ent + (int64_t)h * a.ent_stride;
   const int32_t* vidx_h = a.v_idx ? a.v_idx + (int64_t)h * a.v_budget : nullptr;
-  const int vcnt = a.v_idx ? a.v_cnt[h] : 0;
+  const int vcnt = a.v_idx ? __builtin_amdgcn_readfirstlane(a.v_cnt[h]) : 0;
   const int n_vt = (vcnt + 63) >> 6;
   const int cc_limit = m0 + NQB;  // cc = c + NQB - 1, c <= m0
 
@@ -131,19 +145,34 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
 
-  // ---- tile iterator (uniform over the workgroup) -----------------------------------------
-  // kind 0: slash tile, idx = cc; kind 1: vertical tile, idx = vt; kind 2: end
-  auto advance = [&](int& kind, int& idx) {
-    if (kind == 0) {
-      int cc = bm_next(bmU, idx + 1, cc_limit);
-      if (cc < cc_limit) { idx = cc; return; }
-      kind = 1; idx = -1;
+  // ---- tile iterator (uniform over the workgroup, kept in scalar registers) -----------------
+  // kind 0: slash tile, idx = cc, mask = query blocks that use it; kind 1: vertical tile,
+  // idx = vt; kind 2: end.  Entries are fetched 64 at a time (one per lane), one batch ahead.
+  uint32_t ecache = ent_h[lane], ecache_nx = ent_h[64 + lane];
+  int ei = -1;
+  auto advance = [&](int& kind, int& idx, int& mask) {
+    int k2 = kind, i2 = idx, m2 = 0;
+    if (k2 == 0) {
+      ++ei;
+      if (__builtin_expect((ei & 63) == 0 && ei > 0, 0)) {
+        ecache = ecache_nx;
+        ecache_nx = ent_h[(ei & ~63) + 64 + lane];
+      }
+      const uint32_t e = __builtin_amdgcn_readlane(ecache, ei & 63);
+      const int cc = (int)(e >> 4);
+      if (cc < cc_limit) { i2 = cc; m2 = (int)(e & 15u); }
+      else { k2 = 1; i2 = -1; }
     }
-    if (kind == 1) {
-      int vt = idx + 1;
-      if (vt < n_vt && (int64_t)vidx_h[64 * vt] <= last_pos) { idx = vt; return; }
+    if (k2 == 1) {
+      const int vt = i2 + 1;
+      bool more = vt < n_vt;
+      if (more) more = (int64_t)__builtin_amdgcn_readfirstlane(vidx_h[64 * vt]) <= last_pos;
+      if (more) i2 = vt; else { k2 = 2; i2 = 0; }
     }
-    kind = 2; idx = 0;
+    // the descriptor is uniform by construction; say so, so that it lives in scalar registers
+    kind = __builtin_amdgcn_readfirstlane(k2);
+    idx = __builtin_amdgcn_readfirstlane(i2);
+    mask = __builtin_amdgcn_readfirstlane(m2);
   };
   // key index that tile row r comes from (general path)
   auto src_row = [&](int kind, int idx, int r) -> int64_t {
@@ -155,65 +184,78 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     return pos < vcnt ? (int64_t)vidx_h[pos] : 0;
   };
 
-  // ---- staging: global -> registers -> LDS ------------------------------------------------
-  // chunk x = tid + e NT of a tile: row x / DCH, 16-byte chunk x % DCH
-  uint32_t koff[CPT], voff[CPT];  // byte offsets inside a contiguous 64-key block
-#pragma unroll
-  for (int e = 0; e < CPT; ++e) {
-    const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
-    koff[e] = (uint32_t)(r * a.k_stride_tok * 2 + ch * 16);
-    voff[e] = (uint32_t)(r * a.v_stride_tok * 2 + ch * 16);
-  }
-  u32x4 kst[CPT], vst[CPT];
-  int32_t my_vidx = 0;
-  auto load_tile = [&](int kind, int idx) {
+  // ---- staging: global -> LDS copies, GPW groups of RPG rows per wave for K and for V --------
+  // wave wv copies groups q = e * (2 NQB) + wv, e = 0..GPW-1; with this interleaving the
+  // swizzle of a lane's row does not depend on e, so one 32-bit offset per lane serves all
+  // its copies and the e-dependent part stays in scalar registers.
+  constexpr int WAVES = 2 * NQB;
+  const int lr = lane / DCH, lc = lane % DCH;  // this lane's row inside a group, and its LDS slot
+  const int r0 = wv * RPG + lr;                // its row in the group e = 0
+  const int kch = lc ^ ((r0 / R) % DCH);       // d-chunk it fetches for K (after the swizzle)
+  const int vch = lc ^ ((((r0 / R) & 3) << 2) & (DCH - 1));  // ... and for V
+  static_assert((WAVES * RPG / R) % DCH == 0 && (WAVES * RPG / R) % 4 == 0, "swizzle must not depend on e");
+  const uint32_t koff = (uint32_t)(r0 * a.k_stride_tok * 2 + kch * 16);
+  const uint32_t voff = (uint32_t)(r0 * a.v_stride_tok * 2 + vch * 16);
+  auto issue_tile = [&](int kind, int idx, int buf) {
+    const uint32_t kdst = ks_addr + (uint32_t)(buf * TILE * 2 + wv * 1024);
+    const uint32_t vdst = vs_addr + (uint32_t)(buf * TILE * 2 + wv * 1024);
+    bool fast = false;
     if (kind == 0) {
       const int64_t j0 = (int64_t)(m0 - (idx - (NQB - 1))) * 64;
-      if (j0 + 64 <= n_k) {  // whole block in range: one uniform base + per-thread 32-bit offsets
+      if (__builtin_expect(j0 + 64 <= n_k, 1)) {  // whole block in range: uniform bases + one per-lane 32-bit offset
+        fast = true;
         const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
         const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) kst[e] = *(const u32x4*)(kt + koff[e]);
+        for (int e = 0; e < GPW; ++e)
+          dma16_uniform_base(kdst + e * WAVES * 1024, kt + (int64_t)e * WAVES * RPG * a.k_stride_tok * 2, koff);
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) vst[e] = *(const u32x4*)(vt + voff[e]);
-        return;
+        for (int e = 0; e < GPW; ++e)
+          dma16_uniform_base(vdst + e * WAVES * 1024, vt + (int64_t)e * WAVES * RPG * a.v_stride_tok * 2, voff);
       }
     }
+    if (__builtin_expect(!fast, 0)) {
 #pragma unroll
-    for (int e = 0; e < CPT; ++e) {
-      const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
-      const int64_t j = src_row(kind, idx, r);
-      kst[e] = *(const u32x4*)(kbase + j * a.k_stride_tok + ch * 8);
-      vst[e] = *(const u32x4*)(vbase + j * a.v_stride_tok + ch * 8);
+      for (int e = 0; e < GPW; ++e) {
+        const int64_t j = src_row(kind, idx, e * WAVES * RPG + r0);
+        dma16_lane_ptr(kdst + e * WAVES * 1024, kbase + j * a.k_stride_tok + kch * 8);
+        dma16_lane_ptr(vdst + e * WAVES * 1024, vbase + j * a.v_stride_tok + vch * 8);
+      }
+      if (kind == 1 && tid < 64) vidx_s[buf * 64 + tid] = (int32_t)src_row(kind, idx, tid);
     }
-    if (kind == 1 && tid < 64) my_vidx = (int32_t)src_row(kind, idx, tid);
   };
-  auto store_tile = [&](int buf, int kind) {
-#pragma unroll
-    for (int e = 0; e < CPT; ++e) {
-      const int x = tid + e * NT, r = x / DCH, ch = x % DCH;
-      *(u32x4*)&Ks[buf * KBUF + r * KS + ch * 8] = kst[e];
-      *(u32x4*)&Vs[buf * VBUF + r * VR + ch * 8] = vst[e];
-    }
-    if (kind == 1 && tid < 64) vidx_s[buf * 64 + tid] = my_vidx;
-  };
+  auto wait_copies = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
 
-  // per-lane LDS element offsets of the MFMA operands
-  const int k_lane = (lane & 31) * KS + 8 * hh;  // K rows as A operand of S^T = K Q^T
+  // ---- per-lane LDS element offsets of the MFMA operands -------------------------------------
+  // K rows as A operand of S^T = K Q^T: lane (j = lane%32, hh) reads d-chunk 2 st + hh of row j
+  int k_ofs[DSTEPS];
+  {
+    const int y = hh ^ (((lane & 31) / R) % DCH);
+#pragma unroll
+    for (int st = 0; st < DSTEPS; ++st) k_ofs[st] = (lane & 31) * D + ((2 * st) ^ y) * 8;
+  }
   // V^T operand through the transposing LDS read: inside each 16-lane group, lane L supplies
-  // the address of V[J0 + L/4][D0 + 4 (L%4) .. +3] and receives V[J0 .. J0+3][D0 + L]
-  const int v_lane = (((lane & 15) >> 2) + 4 * hh) * VR + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  // the address of V[J0 + L/4][D0 + 4 (L%4) .. +3] and receives V[J0 .. J0+3][D0 + L];
+  // D0 = 32 db + 16 * (group & 1), J0 = (multiple of 8) + 4 hh.
+  int v_ofs[DB];
+  {
+    const int rl = ((lane & 15) >> 2) + 4 * hh;
+    const int gl = (((rl / R) & 3) << 2) & (DCH - 1);
+    const int ul = 2 * ((lane >> 4) & 1) + ((lane >> 1) & 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) v_ofs[db] = rl * D + (((4 * db + ul) ^ gl) * 8) + 4 * (lane & 1);
+  }
 
   auto qk_step = [&](f32x16& acc, const __bf16* kb, int jb, int st) {
-    const bf16x8 ka = *(const bf16x8*)&kb[k_lane + 32 * jb * KS + 16 * st];
+    const bf16x8 ka = *(const bf16x8*)&kb[k_ofs[st] + 32 * jb * D];
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[st], acc, 0, 0, 0);
   };
   // keys of MFMA k-slots 8 hh + 0..7 in step tt of key block jb: 32 jb + 16 tt + 8 (e/4) + 4 hh + e%4
   auto pv_step = [&](const __bf16* vb, const bf16x8 pb, int jb, int tt, int db) {
     typedef bf16x4 __attribute__((address_space(3))) * lds_b4;
-    const __bf16* p0 = &vb[v_lane + (32 * jb + 16 * tt) * VR + 32 * db];
+    const __bf16* p0 = &vb[v_ofs[db] + (32 * jb + 16 * tt) * D];
     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0 + 8 * VR));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0 + 8 * D));
     const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[db], 0, 0, 0);
   };
@@ -226,13 +268,13 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // running-max update with the maximum of a block of scores (base-2 domain).  When some row's
   // maximum grows, everything already expressed relative to the old maximum is rescaled: the
   // row sum, O, and `pend` (probabilities computed but not yet multiplied into O) if has_pend.
-  auto update_max_impl = [&](float mx, f32x16& pend, const bool has_pend) -> float {
+  auto update_max = [&](float mx, f32x16& pend, const bool has_pend) -> float {
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, mx * a.scale_log2);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
     m_run = m_new;
-    if (__any(alpha != 1.0f)) {
+    if (__builtin_expect(__any(alpha != 1.0f), 0)) {
       l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -262,134 +304,111 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     l_run += ps;
   };
 
-  // ---- prologue: tile 0 -> LDS buffer 0, tile 1 -> registers ---------------------------------
-  int cur_kind = 0, cur_idx = -1;
-  advance(cur_kind, cur_idx);
+  // ---- prologue: tile 0 -> LDS buffer 0 -------------------------------------------------------
+  int cur_kind = 0, cur_idx = -1, cur_mask = 0;
+  advance(cur_kind, cur_idx, cur_mask);
+  int nxt_kind = cur_kind, nxt_idx = cur_idx, nxt_mask = cur_mask;
   if (cur_kind != 2) {
-    load_tile(cur_kind, cur_idx);
-    store_tile(0, cur_kind);
+    issue_tile(cur_kind, cur_idx, 0);
+    advance(nxt_kind, nxt_idx, nxt_mask);
   }
-  int nxt_kind = cur_kind, nxt_idx = cur_idx;
-  if (cur_kind != 2) {
-    advance(nxt_kind, nxt_idx);
-    if (nxt_kind != 2) load_tile(nxt_kind, nxt_idx);
-  }
+  wait_copies();
   __syncthreads();
   int buf = 0;
 
   while (cur_kind != 2) {
-    const __bf16* kb = Ks + buf * KBUF;
-    const __bf16* vb = Vs + buf * VBUF;
+    // the copy of the next tile into the other buffer runs under this tile's arithmetic
+    if (nxt_kind != 2 && !(a.dbg & 1)) issue_tile(nxt_kind, nxt_idx, buf ^ 1);
+
+    const __bf16* kb = Ks + buf * TILE;
+    const __bf16* vb = Vs + buf * TILE;
     // ---- does this wave take part, and with which element mask? ----------------------
+    // A masked tile gives every key r of the tile a threshold need[r]: row il of the query
+    // block may use it iff il >= need[r] (64 = never).  Slash tile on the block's own diagonal:
+    // need[r] = r.  Vertical tile: 0 for a column of an earlier, uncovered key block; the
+    // column's offset inside the block when it lies in the query block's own key block; 64
+    // when it is out of range, in a later block, or already covered by a computed diagonal.
     bool part = wave_valid;
-    bool diag = false;            // slash tile on the query block's own diagonal
-    uint64_t vmask = ~0ull;       // vertical tile: keys this query block may use
-    uint64_t dmask = 0;           // vertical tile: keys inside the query block's own key block
-    if (cur_kind == 0) {
-      const int ad = cur_idx - (NQB - 1) + t;  // block diagonal of (query block t, this key block)
-      part = part && ad >= 0 && bm_test(bmA, ad);
-      diag = ad == 0;
+    bool diag = false;
+    if (__builtin_expect(cur_kind == 0, 1)) {
+      part = part && ((cur_mask >> t) & 1);
+      diag = cur_idx - (NQB - 1) + t == 0;  // block diagonal 0 of (query block t, this key block)
     } else {
       const int pos = 64 * cur_idx + lane;
       const int j = vidx_s[buf * 64 + lane];
       const int ad = (m0 + t) - (j >> 6);
-      const bool ok = pos < vcnt && ad >= 0 && !bm_test(bmA, ad);
-      vmask = __ballot(ok);
-      dmask = __ballot(ok && ad == 0);
-      part = part && vmask != 0;
+      int need = 64;
+      if (pos < vcnt && ad >= 0 && !bm_test(bmA, ad)) need = ad == 0 ? (j & 63) : 0;
+      need_s[wv * 64 + lane] = (uint8_t)need;
+      part = part && __ballot(need < 64) != 0;
     }
-    const bool masked = diag || cur_kind == 1;
+    const bool vert = cur_kind == 1;
 
-    f32x16 s[2];
-    if (part) {
+    // element x of block jb is key r = 32 jb + 8 (x/4) + 4 hh + (x%4) of the tile
+    auto apply_mask = [&](f32x16& sv, int jb) {
+      if (diag) {
 #pragma unroll
-      for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) s[jb][x] = 0.f;
-      if (!masked) {
-        // -------- fast path: the two 32-key halves are software-pipelined --------------
-        // S0; first half of S1 ahead of the max of S0; exp(S0) under the rest of S1;
-        // PV(0) under exp(S1); PV(1) after the staging below.
-#pragma unroll
-        for (int st = 0; st < DSTEPS; ++st) qk_step(s[0], kb, 0, st);
-#pragma unroll
-        for (int st = 0; st < DSTEPS / 2; ++st) qk_step(s[1], kb, 1, st);
-        const float mu0 = update_max_impl(block_max(s[0]), s[0], false);
-#pragma unroll
-        for (int st = DSTEPS / 2; st < DSTEPS; ++st) qk_step(s[1], kb, 1, st);
-        exp_block(s[0], mu0);
-        // P0 is relative to the old maximum: if S1 raises it, P0 is rescaled with O before PV(0)
-        const float mu1 = update_max_impl(block_max(s[1]), s[0], true);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 pb = to_bf16(s[0], tt);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
+        for (int x = 0; x < 16; ++x) {
+          const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
+          if (r > il) sv[x] = -INFINITY;
         }
-        exp_block(s[1], mu1);
       } else {
-        // -------- masked tile (own diagonal block, or gathered columns): plain order ------
 #pragma unroll
-        for (int jb = 0; jb < 2; ++jb)
+        for (int xq = 0; xq < 4; ++xq) {
+          const uint32_t nd = *(const uint32_t*)&need_s[wv * 64 + 32 * jb + 8 * xq + 4 * hh];
 #pragma unroll
-          for (int st = 0; st < DSTEPS; ++st) qk_step(s[jb], kb, jb, st);
-        // element x of block jb is key r = 32 jb + 8 (x/4) + 4 hh + (x%4) of the tile
-        if (diag) {
-#pragma unroll
-          for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-              const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-              if (r > il) s[jb][x] = -INFINITY;
-            }
-        } else {
-#pragma unroll
-          for (int jb = 0; jb < 2; ++jb) {
-            const uint32_t vb_ = (uint32_t)(vmask >> (32 * jb + 4 * hh));
-            const uint32_t db_ = (uint32_t)(dmask >> (32 * jb + 4 * hh));
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-              const int bit = 8 * (x >> 2) + (x & 3);
-              bool ok = (vb_ >> bit) & 1u;
-              if (dmask != 0 && ((db_ >> bit) & 1u)) {
-                const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-                ok = ok && (vidx_s[buf * 64 + r] & 63) <= il;
-              }
-              if (!ok) s[jb][x] = -INFINITY;
-            }
-          }
-        }
-        const float mu = update_max_impl(fmaxf(block_max(s[0]), block_max(s[1])), s[0], false);
-        exp_block(s[0], mu);
-        exp_block(s[1], mu);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 pb = to_bf16(s[0], tt);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
+          for (int x = 0; x < 4; ++x)
+            if (il < (int)((nd >> (8 * x)) & 255u)) sv[4 * xq + x] = -INFINITY;
         }
       }
-    }
+    };
 
-    // ---- staging: next tile registers -> other LDS buffer; tile after next -> registers ----
-    int nn_kind = nxt_kind, nn_idx = nxt_idx;
-    if (nxt_kind != 2) {
-      store_tile(buf ^ 1, nxt_kind);
-      advance(nn_kind, nn_idx);
-      if (nn_kind != 2) load_tile(nn_kind, nn_idx);
-    }
-
-    if (part) {
+    if (part && !(a.dbg & 8)) {
+      // The two 32-key halves are software-pipelined: S0; first half of S1 ahead of the max of
+      // S0; exp(S0) under the rest of S1; PV(0) under exp(S1); then PV(1).  The scheduling
+      // fences keep the compiler from hoisting every LDS read to the top.
+      f32x16 s0, s1;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
+#pragma unroll
+      for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int st = 0; st < DSTEPS / 2; ++st) qk_step(s1, kb, 1, st);
+      __builtin_amdgcn_sched_barrier(0);
+      if (__builtin_expect(diag || vert, 0)) apply_mask(s0, 0);
+      const float mu0 = update_max(block_max(s0), s0, false);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int st = DSTEPS / 2; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
+      exp_block(s0, mu0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (__builtin_expect(diag || vert, 0)) apply_mask(s1, 1);
+      // P0 is relative to the old maximum: if S1 raises it, P0 is rescaled with O before PV(0)
+      const float mu1 = update_max(block_max(s1), s0, true);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8 pb = to_bf16(s[1], tt);
+        const bf16x8 pb = to_bf16(s0, tt);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
+      }
+      exp_block(s1, mu1);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 pb = to_bf16(s1, tt);
 #pragma unroll
         for (int db = 0; db < DB; ++db) pv_step(vb, pb, 1, tt, db);
       }
     }
-    __syncthreads();
-    cur_kind = nxt_kind; cur_idx = nxt_idx;
-    nxt_kind = nn_kind; nxt_idx = nn_idx;
+
+    int nn_kind = nxt_kind, nn_idx = nxt_idx, nn_mask = nxt_mask;
+    if (nxt_kind != 2) advance(nn_kind, nn_idx, nn_mask);
+    if (!(a.dbg & 2)) wait_copies();
+    if (!(a.dbg & 4)) __syncthreads();
+    cur_kind = nxt_kind; cur_idx = nxt_idx; cur_mask = nxt_mask;
+    nxt_kind = nn_kind; nxt_idx = nn_idx; nxt_mask = nn_mask;
     buf ^= 1;
   }
 
@@ -414,18 +433,23 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Bitmaps of block diagonals from the selected slash offsets (one workgroup per head).
+// Block list of one head from its selected slash offsets (one workgroup per head).
 // Offset o crosses, inside a 64-aligned query block, the key blocks of diagonals floor(o/64)
-// and, when o is not a multiple of 64, floor(o/64) + 1.
+// and, when o is not a multiple of 64, floor(o/64) + 1: these set the bitmap A.  The entry
+// list then holds every cc for which A has a bit in [cc - (NQB-1), cc], with the per-query-
+// block mask, in ascending order, followed by sentinels up to the end of the row.
 // ---------------------------------------------------------------------------------------------
 template <int NQB>
-__global__ __launch_bounds__(256) void k_build_bitmaps(const int32_t* s_idx, const int32_t* s_cnt,
-                                                       int32_t s_budget, int dense, int n_blk,
-                                                       int n_words, uint32_t* bm_a, uint32_t* bm_u) {
-  const int h = blockIdx.x;
+__global__ __launch_bounds__(256) void k_build_blocklist(const int32_t* s_idx, const int32_t* s_cnt,
+                                                         int32_t s_budget, int dense, int n_blk,
+                                                         int n_words, int ent_stride, uint32_t* bm_a,
+                                                         uint32_t* ent) {
+  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   uint32_t* A = bm_a + (int64_t)h * n_words;
-  uint32_t* U = bm_u + (int64_t)h * n_words;
-  for (int w = threadIdx.x; w < n_words; w += blockDim.x) {
+  uint32_t* E = ent + (int64_t)h * ent_stride;
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t running;
+  for (int w = tid; w < n_words; w += 256) {
     uint32_t x = 0;
     if (dense) {
       const int lo = w * 32;
@@ -434,25 +458,51 @@ __global__ __launch_bounds__(256) void k_build_bitmaps(const int32_t* s_idx, con
     }
     A[w] = x;
   }
+  if (tid == 0) running = 0;
   __syncthreads();
   if (!dense) {
     const int cnt = s_cnt[h];
     const int32_t* so = s_idx + (int64_t)h * s_budget;
-    for (int i = threadIdx.x; i < cnt; i += blockDim.x) {
+    for (int i = tid; i < cnt; i += 256) {
       const int o = so[i], ad = o >> 6;
       if (ad < n_blk) atomicOr(&A[ad >> 5], 1u << (ad & 31));
       if ((o & 63) && ad + 1 < n_blk) atomicOr(&A[(ad + 1) >> 5], 1u << ((ad + 1) & 31));
     }
     __syncthreads();
   }
-  // U bit cc = OR of A bits cc-(NQB-1) .. cc
-  for (int w = threadIdx.x; w < n_words; w += blockDim.x) {
-    const uint32_t cur = A[w], prev = w ? A[w - 1] : 0u;
+  // ordered compaction of the U bits, 256 words per round
+  for (int w0 = 0; w0 < n_words; w0 += 256) {
+    const int w = w0 + tid;
+    uint32_t cur = 0, prev = 0;
+    if (w < n_words) { cur = A[w]; prev = w ? A[w - 1] : 0u; }
     uint32_t u = cur;
 #pragma unroll
     for (int sft = 1; sft < NQB; ++sft) u |= (cur << sft) | (prev >> (32 - sft));
-    U[w] = u;
+    const uint32_t c = __popc(u);
+    // exclusive scan of c over the workgroup
+    uint32_t inc = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t y = __shfl_up(inc, d);
+      if (lane >= d) inc += y;
+    }
+    if (lane == 63) wsum[wv] = inc;
+    __syncthreads();
+    uint32_t pos = running + inc - c;
+    for (int x = 0; x < wv; ++x) pos += wsum[x];
+    const uint64_t a64 = ((uint64_t)cur << 32) | prev;  // bit (32 + b) = A bit 32 w + b
+    while (u) {
+      const int b = __builtin_ctz(u);
+      u &= u - 1;
+      // mask bit t = A bit (32 w + b - (NQB-1) + t)
+      const uint32_t mask = (uint32_t)(a64 >> (32 + b - (NQB - 1))) & ((1u << NQB) - 1u);
+      E[pos++] = ((uint32_t)(32 * w + b) << 4) | mask;
+    }
+    __syncthreads();
+    if (tid == 255) running = pos;
+    __syncthreads();
   }
+  for (int i = running + tid; i < ent_stride; i += 256) E[i] = kEntSentinel;
 }
 
 // Issued-tile accounting, one workgroup per head: for every query block of the chunk, the
@@ -498,20 +548,18 @@ __global__ __launch_bounds__(256) void k_count_tiles(const int32_t* v_idx, const
 }
 
 // ---------------------------------------------------------------------------------------------
-hipError_t launch_build_bitmaps(const vs_params& p, const int32_t* s_idx, const int32_t* s_cnt,
-                                bool dense, uint32_t* bm_a, uint32_t* bm_u, hipStream_t st) {
+hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, const int32_t* s_cnt,
+                                  bool dense, const BlockList& bl, hipStream_t st) {
   const int64_t n_k = p.q_start + p.q_len;
-  const int n_blk = (int)ceil_div(n_k, kBlock), n_words = (int)bitmap_words(n_k);
-  const int heads = dense ? 1 : p.n_q_heads;
-  hipLaunchKernelGGL((k_build_bitmaps<kAttnQBlocks>), dim3(heads), dim3(256), 0, st, s_idx, s_cnt,
-                     p.slash_budget, dense ? 1 : 0, n_blk, n_words, bm_a, bm_u);
+  const int n_blk = (int)ceil_div(n_k, kBlock);
+  hipLaunchKernelGGL((k_build_blocklist<kAttnQBlocks>), dim3(bl.heads), dim3(256), 0, st, s_idx, s_cnt,
+                     p.slash_budget, dense ? 1 : 0, n_blk, (int)bl.words, (int)bl.ent_stride, bl.bm_a, bl.ent);
   return hipGetLastError();
 }
 
 hipError_t launch_attention(const vs_params& p, const void* q, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
-                            const uint32_t* bm_a, const uint32_t* bm_u, void* out, float* lse,
-                            hipStream_t st) {
+                            const BlockList& bl, void* out, float* lse, hipStream_t st) {
   constexpr int NQB = kAttnQBlocks;
   AttnArgs a;
   a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v;
@@ -520,14 +568,16 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
   a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
   a.v_stride_tok = p.v_stride_tok; a.v_stride_head = p.v_stride_head;
   a.o_stride_tok = p.o_stride_tok; a.o_stride_head = p.o_stride_head;
-  a.bm_a = bm_a; a.bm_u = bm_u;
-  a.bm_stride = dense ? 0 : bitmap_words(p.q_start + p.q_len);
+  a.bm_a = bl.bm_a; a.ent = bl.ent;
+  a.bm_stride = dense ? 0 : bl.words;
+  a.ent_stride = dense ? 0 : bl.ent_stride;
   a.v_idx = dense ? nullptr : v_idx; a.v_cnt = dense ? nullptr : v_cnt;
   a.v_budget = p.vertical_budget;
   a.n_q_heads = p.n_q_heads; a.n_kv_heads = p.n_kv_heads; a.group = p.n_q_heads / p.n_kv_heads;
   a.n_qtiles = (int)ceil_div(p.q_len, 64 * NQB);
   a.q_len = p.q_len; a.q_start = p.q_start;
   a.scale_log2 = p.softmax_scale * kLog2e;
+  { const char* e = getenv("VS_ATTN_DBG"); a.dbg = e ? atoi(e) : 0; }
   const int64_t groups = (int64_t)a.n_qtiles * p.n_kv_heads;
   const int64_t blocks = ceil_div(groups, 8) * 8 * a.group;
   // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel
@@ -551,10 +601,9 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
 }
 
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,
-                              const uint32_t* bm_a, int64_t* tiles, hipStream_t st) {
+                              const BlockList& bl, int64_t* tiles, hipStream_t st) {
   hipLaunchKernelGGL(k_count_tiles, dim3(p.n_q_heads), dim3(256), 0, st, v_idx, v_cnt,
-                     p.vertical_budget, bm_a, (int)bitmap_words(p.q_start + p.q_len), p.q_start,
-                     p.q_len, tiles);
+                     p.vertical_budget, bl.bm_a, (int)bl.words, p.q_start, p.q_len, tiles);
   return hipGetLastError();
 }
 

@@ -22,23 +22,50 @@ constexpr float kLn2 = 0.6931471805599453f;
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 
-// ---- block-diagonal bitmaps (built per head from the selected slash offsets) ----------
-// A: bit a set <=> block diagonal a is computed.  U: bit cc set <=> some query block t of a
-// tile of NQB query blocks uses key block (m0 - (cc - (NQB-1))), i.e. A has a bit in
-// [cc-NQB+1, cc].  Both are padded so that every word a kernel may touch exists.
-static inline int64_t bitmap_words(int64_t n_k) { return ceil_div(ceil_div(n_k, kBlock) + 8, 32) + 1; }
-
+// ---- block list (built per head from the selected slash offsets) -----------------------
+// A: bitmap, bit a set <=> block diagonal a is computed.
+// ent: ascending list of key-block entries for a query tile of kAttnQBlocks query blocks:
+//   entry = (cc << 4) | mask, cc = c + (kAttnQBlocks - 1); the tile whose first query block is
+//   m0 uses key block m0 - c, and query block t of the tile takes part iff mask bit t is set
+//   (diagonal c + t is in A).  The list is padded with sentinels (cc = 0x7FFFFFF) so that a
+//   reader may fetch whole batches of 64 entries without bounds checks.
 constexpr int kAttnQBlocks = 2;       // query blocks (of 64 rows) per attention workgroup
+constexpr uint32_t kEntSentinel = 0x7FFFFFF0u;
+
+struct BlockList {
+  uint32_t* bm_a;     // [heads][words]
+  uint32_t* ent;      // [heads][ent_stride]
+  int64_t words, ent_stride;
+  int heads;          // n_q_heads, or 1 for the dense list shared by all heads
+};
+static inline int64_t bitmap_words(int64_t n_k) { return ceil_div(ceil_div(n_k, kBlock) + 8, 32) + 2; }
+static inline int64_t entry_stride(int64_t n_k) {
+  return ceil_div(ceil_div(n_k, kBlock) + kAttnQBlocks, 64) * 64 + 128;
+}
+static inline size_t blocklist_bytes(const vs_params& p, bool dense) {
+  const size_t heads = dense ? 1 : (size_t)p.n_q_heads;
+  const int64_t n_k = p.q_start + p.q_len;
+  return align_up(heads * (size_t)bitmap_words(n_k) * 4, 256) + align_up(heads * (size_t)entry_stride(n_k) * 4, 256);
+}
+static inline BlockList blocklist_layout(const vs_params& p, bool dense, void* ws) {
+  BlockList b;
+  const int64_t n_k = p.q_start + p.q_len;
+  b.heads = dense ? 1 : p.n_q_heads;
+  b.words = bitmap_words(n_k);
+  b.ent_stride = entry_stride(n_k);
+  b.bm_a = (uint32_t*)ws;
+  b.ent = (uint32_t*)((char*)ws + align_up((size_t)b.heads * (size_t)b.words * 4, 256));
+  return b;
+}
 
 // ---- launchers (defined in the .hip files; all enqueue on `st`, return hipError_t) ------
-hipError_t launch_build_bitmaps(const vs_params& p, const int32_t* s_idx, const int32_t* s_cnt,
-                                bool dense, uint32_t* bm_a, uint32_t* bm_u, hipStream_t st);
+hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, const int32_t* s_cnt,
+                                  bool dense, const BlockList& bl, hipStream_t st);
 hipError_t launch_attention(const vs_params& p, const void* q, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
-                            const uint32_t* bm_a, const uint32_t* bm_u, void* out, float* lse,
-                            hipStream_t st);
+                            const BlockList& bl, void* out, float* lse, hipStream_t st);
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,
-                              const uint32_t* bm_a, int64_t* tiles, hipStream_t st);
+                              const BlockList& bl, int64_t* tiles, hipStream_t st);
 
 size_t estimate_ws_bytes(const vs_params& p);
 hipError_t launch_estimate(const vs_params& p, const void* q, const void* k, float* vscore,
