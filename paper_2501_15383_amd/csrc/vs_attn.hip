@@ -144,6 +144,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 #pragma unroll
     for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  bool have_max = false;  // every row of this wave has a finite running maximum (uniform)
 
   // ---- tile iterator (uniform over the workgroup, kept in scalar registers) -----------------
   // kind 0: slash tile, idx = cc, mask = query blocks that use it; kind 1: vertical tile,
@@ -246,6 +247,16 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     for (int db = 0; db < DB; ++db) v_ofs[db] = rl * D + (((4 * db + ul) ^ gl) * 8) + 4 * (lane & 1);
   }
 
+  auto k_load = [&](const __bf16* kb, int jb, int st) -> bf16x8 {
+    return *(const bf16x8*)&kb[k_ofs[st] + 32 * jb * D];
+  };
+  auto v_load = [&](const __bf16* vb, int jb, int tt, int db) -> bf16x8 {
+    typedef bf16x4 __attribute__((address_space(3))) * lds_b4;
+    const __bf16* p0 = &vb[v_ofs[db] + (32 * jb + 16 * tt) * D];
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0 + 8 * D));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
   auto qk_step = [&](f32x16& acc, const __bf16* kb, int jb, int st) {
     const bf16x8 ka = *(const bf16x8*)&kb[k_ofs[st] + 32 * jb * D];
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[st], acc, 0, 0, 0);
@@ -265,43 +276,22 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     for (int x = 0; x < 8; ++x) pf[x] = sv[8 * tt + x];
     return __builtin_convertvector(pf, bf16x8);
   };
-  // running-max update with the maximum of a block of scores (base-2 domain).  When some row's
-  // maximum grows, everything already expressed relative to the old maximum is rescaled: the
-  // row sum, O, and `pend` (probabilities computed but not yet multiplied into O) if has_pend.
-  auto update_max = [&](float mx, f32x16& pend, const bool has_pend) -> float {
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx * a.scale_log2);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-    m_run = m_new;
-    if (__builtin_expect(__any(alpha != 1.0f), 0)) {
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
-      if (has_pend) {
-#pragma unroll
-        for (int x = 0; x < 16; ++x) pend[x] *= alpha;
-      }
-    }
-    return m_use;
-  };
   auto block_max = [&](const f32x16& sv) -> float {
     float mx = sv[0];
 #pragma unroll
     for (int x = 1; x < 16; ++x) mx = fmaxf(mx, sv[x]);
     return mx;
   };
-  auto exp_block = [&](f32x16& sv, float m_use) {
+  // sv <- exp2(sv * scale_log2 - m_ref); returns this lane's sum of the 16 probabilities
+  auto exp_block = [&](f32x16& sv, float m_ref) -> float {
     float ps = 0.f;
 #pragma unroll
     for (int x = 0; x < 16; ++x) {
-      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], a.scale_log2, -m_use));
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], a.scale_log2, -m_ref));
       sv[x] = p;
       ps += p;
     }
-    l_run += ps;
+    return ps;
   };
 
   // ---- prologue: tile 0 -> LDS buffer 0 -------------------------------------------------------
@@ -364,42 +354,133 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     };
 
     if (part && !(a.dbg & 8)) {
-      // The two 32-key halves are software-pipelined: S0; first half of S1 ahead of the max of
-      // S0; exp(S0) under the rest of S1; PV(0) under exp(S1); then PV(1).  The scheduling
-      // fences keep the compiler from hoisting every LDS read to the top.
       f32x16 s0, s1;
 #pragma unroll
       for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
+      bool exact = diag || vert || !have_max;
+      if (__builtin_expect(!exact, 1)) {
+        // ---- fast path.  Probabilities are taken relative to the running maximum of the
+        // PREVIOUS tiles (any reference value gives the same softmax; only overflow must be
+        // excluded), so the exponentials do not wait for this tile's maximum and are issued
+        // between the MFMAs:  S0 | S1 with exp(S0) | PV(0) with exp(S1) | PV(1).
+        // The true maximum is folded in after the tile.  If a score exceeds the reference by
+        // more than 2^64 the tile is redone on the exact path below.
+        // Operands are fetched from LDS two MFMAs ahead; the scheduling fences pin this
+        // hand-made interleaving.
+        const float c = a.scale_log2, mref = m_run;
+        constexpr int PF = 4;              // LDS fragments in flight ahead of the MFMAs
+        constexpr int NB = PF + 1;         // rotating fragment registers
+        bf16x8 kf[NB];
 #pragma unroll
-      for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int j = 0; j < PF; ++j) kf[j] = k_load(kb, j / DSTEPS, j % DSTEPS);
 #pragma unroll
-      for (int st = 0; st < DSTEPS / 2; ++st) qk_step(s1, kb, 1, st);
-      __builtin_amdgcn_sched_barrier(0);
-      if (__builtin_expect(diag || vert, 0)) apply_mask(s0, 0);
-      const float mu0 = update_max(block_max(s0), s0, false);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int st = 0; st < DSTEPS; ++st) {
+          const int j = st + PF;
+          kf[j % NB] = k_load(kb, j / DSTEPS, j % DSTEPS);
+          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st % NB], qreg[st], s0, 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        float mx = s0[0], ps = 0.f;
+        constexpr int EPS = 16 / DSTEPS;  // elements of the other half handled per MFMA step
 #pragma unroll
-      for (int st = DSTEPS / 2; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
-      exp_block(s0, mu0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (__builtin_expect(diag || vert, 0)) apply_mask(s1, 1);
-      // P0 is relative to the old maximum: if S1 raises it, P0 is rescaled with O before PV(0)
-      const float mu1 = update_max(block_max(s1), s0, true);
-      __builtin_amdgcn_sched_barrier(0);
+        for (int st = 0; st < DSTEPS; ++st) {
+          const int j = DSTEPS + st + PF;
+          if (j < 2 * DSTEPS) kf[j % NB] = k_load(kb, 1, j - DSTEPS);
+          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(DSTEPS + st) % NB], qreg[st], s1, 0, 0, 0);
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8 pb = to_bf16(s0, tt);
+          for (int x = EPS * st; x < EPS * (st + 1); ++x) {
+            mx = fmaxf(mx, s0[x]);
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[x], c, -mref));
+            s0[x] = p;
+            ps += p;
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        mx = fmaxf(mx, block_max(s1));
+        exact = __any((mx * c > mref + 64.f) | !(ps < 3.0e38f));
+        if (__builtin_expect(!exact, 1)) {
+          constexpr int NPV = 2 * DB;            // PV MFMAs per 32-key half: (tt, db)
+          constexpr int EPV = 16 / NPV;          // exp(S1) elements per MFMA
+          constexpr int VPF = 3, VNB = VPF + 1;  // V fragments (two transposing reads each) in flight
+          bf16x8 vf[VNB], pb;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
+          for (int j = 0; j < VPF; ++j) vf[j] = v_load(vb, j / NPV, (j % NPV) / DB, j % DB);
+#pragma unroll
+          for (int i = 0; i < NPV; ++i) {
+            const int j = i + VPF;               // fragment fetched now: half j / NPV, tt, db
+            vf[j % VNB] = v_load(vb, j / NPV, (j % NPV) / DB, j % DB);
+            if (i % DB == 0) pb = to_bf16(s0, i / DB);
+            oacc[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VNB], pb, oacc[i % DB], 0, 0, 0);
+#pragma unroll
+            for (int x = EPV * i; x < EPV * (i + 1); ++x) {
+              const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[x], c, -mref));
+              s1[x] = p;
+              ps += p;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+#pragma unroll
+          for (int i = 0; i < NPV; ++i) {
+            const int j = NPV + i + VPF;
+            if (j < 2 * NPV) vf[j % VNB] = v_load(vb, 1, (j % NPV) / DB, j % DB);
+            if (i % DB == 0) pb = to_bf16(s1, i / DB);
+            oacc[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[(NPV + i) % VNB], pb, oacc[i % DB], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          l_run += ps;
+          // fold this tile's maximum into the running maximum (rescales only when it grew)
+          const float mrow = fmaxf(mx, __shfl_xor(mx, 32)) * c;
+          if (__builtin_expect(__any(mrow > m_run), 0)) {
+            const float m_new = fmaxf(m_run, mrow);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+              for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
+          }
+        } else {
+#pragma unroll
+          for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
+        }
       }
-      exp_block(s1, mu1);
-      __builtin_amdgcn_sched_barrier(0);
+      if (__builtin_expect(exact, 0)) {
+        // ---- exact path: masked tiles, the first tile(s) of a row block, overflow guard ----
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const bf16x8 pb = to_bf16(s1, tt);
+        for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
 #pragma unroll
-        for (int db = 0; db < DB; ++db) pv_step(vb, pb, 1, tt, db);
+        for (int st = 0; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
+        if (diag || vert) {
+          apply_mask(s0, 0);
+          apply_mask(s1, 1);
+        }
+        float mx = fmaxf(block_max(s0), block_max(s1));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * a.scale_log2);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
+        l_run += exp_block(s0, m_use);
+        l_run += exp_block(s1, m_use);
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const bf16x8 pb = to_bf16(s0, tt);
+#pragma unroll
+          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
+        }
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          const bf16x8 pb = to_bf16(s1, tt);
+#pragma unroll
+          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 1, tt, db);
+        }
+        have_max = !__any(m_run == -INFINITY);
       }
     }
 
