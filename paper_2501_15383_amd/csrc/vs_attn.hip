@@ -20,12 +20,15 @@
 //  * K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4, no staging
 //    registers), double-buffered: the copy of tile t+1 runs under the MFMA work of tile t,
 //    one barrier per tile.  Rows are unpadded; 16-byte chunks are XOR-swizzled instead.
-//  * inside a tile the two 32-key halves are software-pipelined (QK^T of the second half
-//    under the softmax of the first).
+//  * the exponentials of a tile use the running maximum of the previous tiles as reference
+//    (exact path kept for masked tiles, first tiles and an overflow guard), which takes the
+//    row maximum off the critical path; inside a tile the MFMAs of one 32-key half are
+//    interleaved by hand with the exponentials of the other half, operands two to four
+//    LDS reads ahead.
+//  * the tile walk reads a per-head list of (key block, query-block mask) entries through
+//    a 64-entry lane cache and lives entirely in scalar registers.
 //  * blockIdx -> (tile, head): the G heads that share a KV head and the same query tile run
 //    on one XCD back to back (shared L2), heaviest (latest) query tiles first.
-#include <stdlib.h>
-
 #include "vs_common.h"
 
 namespace vs {
@@ -49,7 +52,6 @@ struct AttnArgs {
   int32_t n_qtiles;
   int64_t q_len, q_start;
   float scale_log2;  // softmax_scale * log2(e)
-  int dbg;
 };
 
 __device__ __forceinline__ bool bm_test(const uint32_t* bm, int i) {
@@ -308,7 +310,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 
   while (cur_kind != 2) {
     // the copy of the next tile into the other buffer runs under this tile's arithmetic
-    if (nxt_kind != 2 && !(a.dbg & 1)) issue_tile(nxt_kind, nxt_idx, buf ^ 1);
+    if (nxt_kind != 2) issue_tile(nxt_kind, nxt_idx, buf ^ 1);
 
     const __bf16* kb = Ks + buf * TILE;
     const __bf16* vb = Vs + buf * TILE;
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       }
     };
 
-    if (part && !(a.dbg & 8)) {
+    if (part) {
       f32x16 s0, s1;
 #pragma unroll
       for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
@@ -486,8 +488,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 
     int nn_kind = nxt_kind, nn_idx = nxt_idx, nn_mask = nxt_mask;
     if (nxt_kind != 2) advance(nn_kind, nn_idx, nn_mask);
-    if (!(a.dbg & 2)) wait_copies();
-    if (!(a.dbg & 4)) __syncthreads();
+    wait_copies();
+    __syncthreads();
     cur_kind = nxt_kind; cur_idx = nxt_idx; cur_mask = nxt_mask;
     nxt_kind = nn_kind; nxt_idx = nn_idx; nxt_mask = nn_mask;
     buf ^= 1;
@@ -658,7 +660,6 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
   a.n_qtiles = (int)ceil_div(p.q_len, 64 * NQB);
   a.q_len = p.q_len; a.q_start = p.q_start;
   a.scale_log2 = p.softmax_scale * kLog2e;
-  { const char* e = getenv("VS_ATTN_DBG"); a.dbg = e ? atoi(e) : 0; }
   const int64_t groups = (int64_t)a.n_qtiles * p.n_kv_heads;
   const int64_t blocks = ceil_div(groups, 8) * 8 * a.group;
   // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel

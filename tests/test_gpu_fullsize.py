@@ -1,0 +1,129 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times, on sampled outputs the oracle can compute one by one, plus properties that
+hold at any size.  Inputs come from the seeded generator (synthetic stand-ins for the
+post-RoPE Q/K/V of the paper's models)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2501_15383_amd as vs
+import vsgen
+from gpu_util import ATOL, RTOL, check_index_sets, chunk_of, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(rng, c, n):
+    """first / last rows, rows around 64-row block edges and tile (128-row) edges, random rows"""
+    fixed = [0, 1, 63, 64, 127, 128, c // 2 - 1, c // 2, c - 129, c - 65, c - 64, c - 1]
+    rows = sorted(set([r for r in fixed if 0 <= r < c] + rng.choice(c, n, replace=False).tolist()))
+    return np.array(rows, np.int64)
+
+
+def _check_rows(out, lse, ref_out, ref_lse, heads, rows, what):
+    got = np.transpose(f64(out[rows][:, heads]), (1, 0, 2))
+    err = np.abs(got - ref_out)
+    bad = err > ATOL + RTOL * np.abs(ref_out)
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} sampled outputs off, max err {err.max():.4g}"
+    lg = f64(lse[heads][:, rows])
+    assert np.abs(lg - ref_lse).max() < 2e-3, f"{what}: lse max err {np.abs(lg - ref_lse).max():.4g}"
+
+
+def _run_sparse_chunk(name, chunk_index, heads, n_rows, seed):
+    w = vsgen.WORKLOADS[name]
+    ci = chunk_index % w.n_chunks
+    s = ci * w.chunk
+    C, n_k = w.chunk, s + w.chunk
+    dev = torch.device("cuda:0")
+    K, V = vsgen.make_kv(w, n_k, device=dev)
+    Q = vsgen.make_q(w, s, s + C, device=dev)
+    pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, last_q=w.last_q,
+                        vertical_budget=w.vertical_budget, slash_budget=w.slash_budget,
+                        keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
+    ck = chunk_of(pb)
+    vsc, ssc, lse_w = vs.estimate(ck, Q, K, want_lse=True)
+    sets = vs.select(ck, vsc, ssc)
+    out, lse = vs.sparse_attn_prefill(ck, Q, K, V, *sets, want_lse=True)
+    out2, _ = vs.prefill_chunk(ck, Q, K, V)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "vs_prefill_chunk differs from its stages"
+
+    qh, kh, vh = vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V)
+    # ---- estimation and selection of the sampled heads against the oracle
+    rvs, rss, rlse = oracle.estimate(pb, qh, kh, heads=heads)
+    gv, gs = f64(vsc[heads]), f64(ssc[heads])
+    np.testing.assert_allclose(f64(lse_w[heads]), rlse, atol=5e-4, rtol=0)
+    np.testing.assert_allclose(gv.sum(1), min(w.last_q, C), rtol=2e-4)
+    np.testing.assert_allclose(gs.sum(1), min(w.last_q, C), rtol=2e-4)
+    np.testing.assert_allclose(gv, rvs, rtol=1e-3, atol=1e-8)
+    np.testing.assert_allclose(gs, rss, rtol=1e-3, atol=1e-8)
+    sets_h = [x.cpu().numpy() for x in sets]
+    for i, h in enumerate(heads):
+        check_index_sets(rvs[i], sets_h[0][h], sets_h[1][h], w.vertical_budget, w.keep_first_cols, f"{name} head {h} vertical")
+        check_index_sets(rss[i], sets_h[2][h], sets_h[3][h], w.slash_budget, w.keep_local_band, f"{name} head {h} slash")
+    # ---- attention of sampled rows: the oracle is fed the GPU's own index sets
+    rows = _sample_rows(np.random.default_rng(seed), C, n_rows)
+    ref_out, ref_lse = oracle.sparse_attention(pb, qh, kh, vh, *sets_h, heads=heads, rows=rows)
+    _check_rows(out, lse, ref_out, ref_lse, heads, rows, f"{name} chunk {ci}")
+    # ---- at any size: weights of every row sum to one (V == 1 gives out == 1)
+    ones = torch.ones_like(V)
+    o1, _ = vs.sparse_attn_prefill(ck, Q, K, ones, *sets)
+    torch.cuda.synchronize()
+    dev1 = (o1.float() - 1.0).abs().max().item()
+    assert dev1 < 1e-2, f"{name}: rows of P do not sum to one ({dev1})"
+    # ---- recall against the dense kernel on a slice of rows lies in (0, 1]
+    tiles = vs.count_tiles(ck, *sets).cpu().numpy()
+    assert (tiles[:, 0] > 0).all()
+    return dict(out=out, lse=lse, Q=Q, K=K, V=V, ck=ck, pb=pb)
+
+
+def test_dense_7b_64k_sampled_rows():
+    # configuration 1: 32768 queries at q_start 32768, every key attended
+    w = vsgen.WORKLOADS["dense_7b_64k"]
+    s, C = w.chunk, w.chunk
+    dev = torch.device("cuda:0")
+    K, V = vsgen.make_kv(w, s + C, device=dev)
+    Q = vsgen.make_q(w, s, s + C, device=dev)
+    pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale)
+    ck = chunk_of(pb)
+    out, lse = vs.dense_causal_prefill(ck, Q, K, V, want_lse=True)
+    torch.cuda.synchronize()
+    heads = [0, 13, 27]
+    rows = _sample_rows(np.random.default_rng(1), C, 20)
+    ref_out, ref_lse = oracle.dense_attention(pb, vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V), heads=heads, rows=rows)
+    _check_rows(out, lse, ref_out, ref_lse, heads, rows, "dense_7b_64k")
+    # the sparse entry point with every diagonal selected runs the same tiles: identical bits
+    n_k = s + C
+    ck2 = vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, vertical_budget=1, slash_budget=n_k)
+    all_s = torch.arange(n_k, dtype=torch.int32, device=dev).repeat(w.n_q_heads, 1).contiguous()
+    cnt_s = torch.full((w.n_q_heads,), n_k, dtype=torch.int32, device=dev)
+    v_idx = torch.zeros((w.n_q_heads, 1), dtype=torch.int32, device=dev)
+    v_cnt = torch.ones(w.n_q_heads, dtype=torch.int32, device=dev)
+    out2, lse2 = vs.sparse_attn_prefill(ck2, Q, K, V, v_idx, v_cnt, all_s, cnt_s, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse, lse2)
+
+
+def test_sparse_7b_128k_last_chunk():
+    _run_sparse_chunk("7b_128k", -1, heads=[0, 9, 27], n_rows=12, seed=2)      # configuration 2
+
+
+def test_sparse_7b_1m_last_chunk():
+    r = _run_sparse_chunk("7b_1m", -1, heads=[3, 20], n_rows=10, seed=3)       # configuration 3
+    # recall of the sparse result against the dense kernel (softmax_lse of both, "Sparsity
+    # refinement" paragraph) on the first 128 rows of the chunk
+    ck, Q, K, V = r["ck"], r["Q"], r["K"], r["V"]
+    ck_d = vs.Chunk(ck.n_q_heads, ck.n_kv_heads, ck.head_dim, 128, ck.q_start, ck.softmax_scale)
+    _, lse_d = vs.dense_causal_prefill(ck_d, Q[:128], K, V, want_lse=True)
+    torch.cuda.synchronize()
+    rec = torch.exp(r["lse"][:, :128] - lse_d)
+    assert (rec > 0).all() and (rec <= 1 + 1e-3).all()
+
+
+def test_sparse_7b_1m_middle_chunk():
+    _run_sparse_chunk("7b_1m", 15, heads=[11], n_rows=8, seed=4)
+
+
+def test_sparse_14b_1m_last_chunk():
+    _run_sparse_chunk("14b_1m", -1, heads=[7, 38], n_rows=8, seed=5)            # configuration 4
