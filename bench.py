@@ -82,6 +82,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one 1 GiB device copy (the reference kernel that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by KV head with no exchange inside "
@@ -181,6 +184,13 @@ def main():
         torch.cuda.synchronize()
         dense_ms = e[0].elapsed_time(e[1]) / 2
         del out_d
+
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"traffic_k_attention_{w.name}.json")
