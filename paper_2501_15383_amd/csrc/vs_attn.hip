@@ -145,8 +145,25 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int x = 0; x < 16; ++x) oacc[db][x] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  bool have_max = false;  // every row of this wave has a finite running maximum (uniform)
+  // ---- softmax state of this wave's rows, and the tile whose PV contraction is still owed ----
+  // The V^T P^T product of a tile runs one step after its K Q^T product (see the main loop), so
+  // between two steps a wave carries the tile's probabilities as four bf16 MFMA operands and
+  // their row sum.
+  // Probabilities are 2^(score - m_o) with ONE reference m_o per row for accumulators, row sum
+  // and pending tile alike.  Any reference gives the same softmax; it only has to keep the
+  // numbers in range.  m_o is the true maximum of the row's first tile and is raised (with a
+  // rescale, on the exact path only) when a score outruns it by more than 2^64, so the
+  // steady-state path never touches the accumulators except through the MFMAs.
+  float l_run = 0.f;
+  float m_o = -INFINITY;  // scaled reference (log2 domain)
+  bool have_max = false;  // every row of this wave has a finite m_o (uniform)
+  bool pend = false;      // uniform
+  bf16x8 pp[4];           // P^T operands of the pending tile: keys 16 u .. 16 u + 15 (in MFMA k order)
+  float pend_ps = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int x = 0; x < 8; ++x) pp[u][x] = (__bf16)0.f;
 
   // ---- tile iterator (uniform over the workgroup, kept in scalar registers) -----------------
   // kind 0: slash tile, idx = cc, mask = query blocks that use it; kind 1: vertical tile,
@@ -199,19 +216,36 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   static_assert((WAVES * RPG / R) % DCH == 0 && (WAVES * RPG / R) % 4 == 0, "swizzle must not depend on e");
   const uint32_t koff = (uint32_t)(r0 * a.k_stride_tok * 2 + kch * 16);
   const uint32_t voff = (uint32_t)(r0 * a.v_stride_tok * 2 + vch * 16);
-  auto issue_tile = [&](int kind, int idx, int buf) {
+  auto issue_k = [&](int kind, int idx, int buf) {
     const uint32_t kdst = ks_addr + (uint32_t)(buf * TILE * 2 + wv * 1024);
-    const uint32_t vdst = vs_addr + (uint32_t)(buf * TILE * 2 + wv * 1024);
     bool fast = false;
     if (kind == 0) {
       const int64_t j0 = (int64_t)(m0 - (idx - (NQB - 1))) * 64;
       if (__builtin_expect(j0 + 64 <= n_k, 1)) {  // whole block in range: uniform bases + one per-lane 32-bit offset
         fast = true;
         const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
-        const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
 #pragma unroll
         for (int e = 0; e < GPW; ++e)
           dma16_uniform_base(kdst + e * WAVES * 1024, kt + (int64_t)e * WAVES * RPG * a.k_stride_tok * 2, koff);
+      }
+    }
+    if (__builtin_expect(!fast, 0)) {
+#pragma unroll
+      for (int e = 0; e < GPW; ++e) {
+        const int64_t j = src_row(kind, idx, e * WAVES * RPG + r0);
+        dma16_lane_ptr(kdst + e * WAVES * 1024, kbase + j * a.k_stride_tok + kch * 8);
+      }
+      if (kind == 1 && tid < 64) vidx_s[buf * 64 + tid] = (int32_t)src_row(kind, idx, tid);
+    }
+  };
+  auto issue_v = [&](int kind, int idx, int buf) {
+    const uint32_t vdst = vs_addr + (uint32_t)(buf * TILE * 2 + wv * 1024);
+    bool fast = false;
+    if (kind == 0) {
+      const int64_t j0 = (int64_t)(m0 - (idx - (NQB - 1))) * 64;
+      if (__builtin_expect(j0 + 64 <= n_k, 1)) {
+        fast = true;
+        const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
 #pragma unroll
         for (int e = 0; e < GPW; ++e)
           dma16_uniform_base(vdst + e * WAVES * 1024, vt + (int64_t)e * WAVES * RPG * a.v_stride_tok * 2, voff);
@@ -221,10 +255,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 #pragma unroll
       for (int e = 0; e < GPW; ++e) {
         const int64_t j = src_row(kind, idx, e * WAVES * RPG + r0);
-        dma16_lane_ptr(kdst + e * WAVES * 1024, kbase + j * a.k_stride_tok + kch * 8);
         dma16_lane_ptr(vdst + e * WAVES * 1024, vbase + j * a.v_stride_tok + vch * 8);
       }
-      if (kind == 1 && tid < 64) vidx_s[buf * 64 + tid] = (int32_t)src_row(kind, idx, tid);
     }
   };
   auto wait_copies = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70); };  // vmcnt(0)
@@ -263,15 +295,6 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     const bf16x8 ka = *(const bf16x8*)&kb[k_ofs[st] + 32 * jb * D];
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[st], acc, 0, 0, 0);
   };
-  // keys of MFMA k-slots 8 hh + 0..7 in step tt of key block jb: 32 jb + 16 tt + 8 (e/4) + 4 hh + e%4
-  auto pv_step = [&](const __bf16* vb, const bf16x8 pb, int jb, int tt, int db) {
-    typedef bf16x4 __attribute__((address_space(3))) * lds_b4;
-    const __bf16* p0 = &vb[v_ofs[db] + (32 * jb + 16 * tt) * D];
-    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0));
-    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b4)(p0 + 8 * D));
-    const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[db], 0, 0, 0);
-  };
   auto to_bf16 = [&](const f32x16& sv, int tt) -> bf16x8 {
     f32x8 pf;
 #pragma unroll
@@ -296,36 +319,233 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     return ps;
   };
 
-  // ---- prologue: tile 0 -> LDS buffer 0 -------------------------------------------------------
+  // ---- per-step building blocks ----------------------------------------------------------------
+  const float c = a.scale_log2;
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
+  constexpr float kTooLarge = 1.8446744e19f;  // 2^64: a probability above it means the reference is stale
+  // probabilities of score pair (x, x + 1) of sv relative to ref, rounded to bf16 into operand
+  // P0 (x < 8) or P1; the row sum takes the rounded values, the numbers the PV contraction uses
+  auto exp_pair = [&](const f32x16& sv, int x, float ref, bf16x8& P0, bf16x8& P1, float& ps) {
+    f32x2 pf;
+    pf[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], c, -ref));
+    pf[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x + 1], c, -ref));
+    const bf16x2 pk = __builtin_convertvector(pf, bf16x2);
+    ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, ps, false);
+    bf16x8& P = x < 8 ? P0 : P1;
+    P[x & 7] = pk[0];
+    P[(x & 7) + 1] = pk[1];
+  };
+  constexpr int NM = DSTEPS;  // MFMAs of one 32-key half of K Q^T, and of one half of V^T P^T
+  static_assert(2 * DB == DSTEPS, "both contractions of a half take the same number of MFMAs");
+  // V fragment u (0 .. 2 NM - 1) of the pending tile: half u / NM, k-step tt, output block db
+  auto v_frag = [&](const __bf16* vbp, int u) -> bf16x8 { return v_load(vbp, u / NM, (u % NM) / DB, u % DB); };
+
+  // V^T P^T of the pending tile alone (this wave has no K Q^T to pair it with in this step)
+  auto drain = [&](const __bf16* vbp) {
+    constexpr int VPF = 3, VNB = VPF + 1;
+    bf16x8 vf[VNB];
+#pragma unroll
+    for (int j = 0; j < VPF; ++j) vf[j] = v_frag(vbp, j);
+#pragma unroll
+    for (int u = 0; u < 2 * NM; ++u) {
+      if (u + VPF < 2 * NM) vf[(u + VPF) % VNB] = v_frag(vbp, u + VPF);
+      oacc[u % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[u % VNB], pp[u / DB], oacc[u % DB], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run += pend_ps;
+    pend = false;
+  };
+
+  // K Q^T of a masked tile, of the first tile of a row block, or of a tile whose scores
+  // outran the reference: true maximum first, then the exponentials.  Nothing may be pending
+  // (the accumulators must be up to date when the reference moves).  Leaves the tile pending.
+  auto qk_exact = [&](const __bf16* kb, bool diag, bool vert, auto&& apply_mask) {
+    f32x16 s0, s1;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
+#pragma unroll
+    for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
+#pragma unroll
+    for (int st = 0; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
+    if (diag || vert) {
+      apply_mask(s0, 0);
+      apply_mask(s1, 1);
+    }
+    float mx = fmaxf(block_max(s0), block_max(s1));
+    mx = fmaxf(mx, __shfl_xor(mx, 32)) * c;
+    if (!have_max || __any(mx > m_o + 64.f)) {
+      const float m_new = fmaxf(m_o, mx);
+      const float alpha = m_new == m_o ? 1.f : __builtin_amdgcn_exp2f(m_o - m_new);
+      m_o = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
+      have_max = !__any(m_o == -INFINITY);
+    }
+    const float m_use = (m_o == -INFINITY) ? 0.f : m_o;
+    float ps = 0.f;
+#pragma unroll
+    for (int x = 0; x < 16; x += 2) exp_pair(s0, x, m_use, pp[0], pp[1], ps);
+#pragma unroll
+    for (int x = 0; x < 16; x += 2) exp_pair(s1, x, m_use, pp[2], pp[3], ps);
+    pend_ps = ps;
+    pend = true;
+  };
+
+  // K Q^T of an unmasked tile with nothing pending: S(keys 0..31), then S(keys 32..63) with the
+  // exponentials of the first half between its MFMAs.  Returns false if a score outran the
+  // reference (the caller then redoes the tile on the exact path).
+  auto qk_fast = [&](const __bf16* kb) -> bool {
+    constexpr int PF = 3, NB = PF + 1;
+    bf16x8 kf[NB];
+    f32x16 sa, sn;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) { sa[x] = 0.f; sn[x] = 0.f; }
+#pragma unroll
+    for (int j = 0; j < PF; ++j) kf[j] = k_load(kb, j / NM, j % NM);
+#pragma unroll
+    for (int st = 0; st < NM; ++st) {
+      const int j = st + PF;
+      kf[j % NB] = k_load(kb, j / NM, j % NM);
+      sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st % NB], qreg[st], sa, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    float ps = 0.f;
+#pragma unroll
+    for (int st = 0; st < NM; ++st) {
+      const int j = NM + st + PF;
+      if (j < 2 * NM) kf[j % NB] = k_load(kb, 1, j - NM);
+      sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(NM + st) % NB], qreg[st], sn, 0, 0, 0);
+#pragma unroll
+      for (int x = (16 / NM) * st; x < (16 / NM) * (st + 1); x += 2) exp_pair(sa, x, m_o, pp[0], pp[1], ps);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int x = 0; x < 16; x += 2) exp_pair(sn, x, m_o, pp[2], pp[3], ps);
+    if (__builtin_expect(__any(!(ps < kTooLarge)), 0)) return false;
+    pend_ps = ps;
+    pend = true;
+    return true;
+  };
+
+  // The steady state: K Q^T of this tile and V^T P^T of the previous one in one instruction
+  // stream, so that most MFMAs have a share of the softmax arithmetic next to them:
+  //   A  NM MFMAs      QK(keys 0..31)
+  //   B  3 NM / 2      QK(keys 32..63) with a quarter of PV(prev) mixed in | exp of keys 0..31
+  //   C  3 NM / 2      the rest of PV(prev)                               | exp of keys 32..63
+  // LDS operands are fetched PF MFMAs ahead; the scheduling fences pin the interleaving.
+  // Returns false if a score outran the reference; the previous tile is folded in either way.
+  auto fused = [&](const __bf16* kb, const __bf16* vbp) -> bool {
+    constexpr int PF = 3, NB = PF + 1;
+    constexpr int NBQ = NM / 2;  // PV MFMAs mixed into phase B
+    // MFMA n of the step: which operand it takes from LDS
+    auto is_k = [&](int n) -> bool { return n < NM || (n < NM + 3 * NBQ && (n - NM) % 3 != 2); };
+    auto k_index = [&](int n) -> int { return n < NM ? n : NM + 2 * ((n - NM) / 3) + (n - NM) % 3; };  // jb * NM + st
+    auto v_index = [&](int n) -> int { return n < NM + 3 * NBQ ? (n - NM) / 3 : n - NM - 2 * NBQ; };
+    auto frag = [&](int n) -> bf16x8 {
+      if (is_k(n)) return k_load(kb, k_index(n) / NM, k_index(n) % NM);
+      return v_frag(vbp, v_index(n));
+    };
+    bf16x8 fq[NB];
+    f32x16 sa, sn;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) { sa[x] = 0.f; sn[x] = 0.f; }
+#pragma unroll
+    for (int j = 0; j < PF; ++j) fq[j] = frag(j);
+    bf16x8 q0, q1;  // the second half's operands replace pp[0], pp[1], which are spent by then
+    float ps = 0.f;
+    int xa = 0, xb = 0;  // next score pair of each half (compile-time after unrolling)
+#pragma unroll
+    for (int n = 0; n < 4 * NM; ++n) {
+      if (n + PF < 4 * NM) fq[(n + PF) % NB] = frag(n + PF);
+      if (is_k(n)) {
+        const int ki = k_index(n);
+        if (ki < NM) sa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n % NB], qreg[ki], sa, 0, 0, 0);
+        else sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n % NB], qreg[ki - NM], sn, 0, 0, 0);
+      } else {
+        const int u = v_index(n);
+        oacc[u % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[n % NB], pp[u / DB], oacc[u % DB], 0, 0, 0);
+      }
+      if (n >= NM && n < NM + 3 * NBQ) {
+        const int hi = 16 * (n - NM + 1) / (3 * NBQ);
+        for (; xa + 2 <= hi; xa += 2) exp_pair(sa, xa, m_o, q0, q1, ps);
+      } else if (n >= NM + 3 * NBQ) {
+        const int hi = 16 * (n - NM - 3 * NBQ + 1) / (3 * NBQ);
+        for (; xb + 2 <= hi; xb += 2) exp_pair(sn, xb, m_o, pp[0], pp[1], ps);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    l_run += pend_ps;
+    pend = false;
+    if (__builtin_expect(__any(!(ps < kTooLarge)), 0)) return false;
+    pp[2] = pp[0]; pp[3] = pp[1]; pp[0] = q0; pp[1] = q1;
+    pend_ps = ps;
+    pend = true;
+    return true;
+  };
+
+  // ---- prologue: K of tile 0 -> LDS buffer 0 ----------------------------------------------------
   int cur_kind = 0, cur_idx = -1, cur_mask = 0;
   advance(cur_kind, cur_idx, cur_mask);
   int nxt_kind = cur_kind, nxt_idx = cur_idx, nxt_mask = cur_mask;
   if (cur_kind != 2) {
-    issue_tile(cur_kind, cur_idx, 0);
+    issue_k(cur_kind, cur_idx, 0);
     advance(nxt_kind, nxt_idx, nxt_mask);
   }
   wait_copies();
   __syncthreads();
   int buf = 0;
 
-  while (cur_kind != 2) {
-    // the copy of the next tile into the other buffer runs under this tile's arithmetic
-    if (nxt_kind != 2) issue_tile(nxt_kind, nxt_idx, buf ^ 1);
-
-    const __bf16* kb = Ks + buf * TILE;
-    const __bf16* vb = Vs + buf * TILE;
-    // ---- does this wave take part, and with which element mask? ----------------------
-    // A masked tile gives every key r of the tile a threshold need[r]: row il of the query
-    // block may use it iff il >= need[r] (64 = never).  Slash tile on the block's own diagonal:
-    // need[r] = r.  Vertical tile: 0 for a column of an earlier, uncovered key block; the
-    // column's offset inside the block when it lies in the query block's own key block; 64
-    // when it is out of range, in a later block, or already covered by a computed diagonal.
-    bool part = wave_valid;
-    bool diag = false;
+  // Step i multiplies K of tile i (LDS buffer i % 2) with Q and V of tile i - 1 (buffer
+  // (i - 1) % 2) with its probabilities.  The copies of K(i + 1) and V(i) into the two free
+  // buffers run under this arithmetic; one barrier per step.  One extra step after the last
+  // tile drains the pipeline.
+  bool last = false, part = false, diag = false, vert = false;
+  const __bf16* kb = Ks;
+  const __bf16* vbp = Vs;
+  // element x of block jb is key r = 32 jb + 8 (x/4) + 4 hh + (x%4) of the tile
+  auto apply_mask = [&](f32x16& sv, int jb) {
+    if (diag) {
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
+        if (r > il) sv[x] = -INFINITY;
+      }
+    } else {
+#pragma unroll
+      for (int xq = 0; xq < 4; ++xq) {
+        const uint32_t nd = *(const uint32_t*)&need_s[wv * 64 + 32 * jb + 8 * xq + 4 * hh];
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+          if (il < (int)((nd >> (8 * x)) & 255u)) sv[4 * xq + x] = -INFINITY;
+      }
+    }
+  };
+  // start of a step: launch the copies, find out whether this wave takes part in tile i and
+  // with which element mask.  A masked tile gives every key r of the tile a threshold need[r]:
+  // row il of the query block may use it iff il >= need[r] (64 = never).  Slash tile on the
+  // block's own diagonal: need[r] = r.  Vertical tile: 0 for a column of an earlier, uncovered
+  // key block; the column's offset inside the block when it lies in the query block's own key
+  // block; 64 when it is out of range, in a later block, or already covered by a computed
+  // diagonal.
+  auto begin_step = [&]() {
+    last = cur_kind == 2;
+    if (!last) {
+      if (nxt_kind != 2) issue_k(nxt_kind, nxt_idx, buf ^ 1);
+      issue_v(cur_kind, cur_idx, buf);
+    }
+    kb = Ks + buf * TILE;
+    vbp = Vs + (buf ^ 1) * TILE;
+    part = wave_valid && !last;
+    diag = false;
     if (__builtin_expect(cur_kind == 0, 1)) {
       part = part && ((cur_mask >> t) & 1);
       diag = cur_idx - (NQB - 1) + t == 0;  // block diagonal 0 of (query block t, this key block)
-    } else {
+    } else if (!last) {
       const int pos = 64 * cur_idx + lane;
       const int j = vidx_s[buf * 64 + lane];
       const int ad = (m0 + t) - (j >> 6);
@@ -334,158 +554,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       need_s[wv * 64 + lane] = (uint8_t)need;
       part = part && __ballot(need < 64) != 0;
     }
-    const bool vert = cur_kind == 1;
-
-    // element x of block jb is key r = 32 jb + 8 (x/4) + 4 hh + (x%4) of the tile
-    auto apply_mask = [&](f32x16& sv, int jb) {
-      if (diag) {
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-          if (r > il) sv[x] = -INFINITY;
-        }
-      } else {
-#pragma unroll
-        for (int xq = 0; xq < 4; ++xq) {
-          const uint32_t nd = *(const uint32_t*)&need_s[wv * 64 + 32 * jb + 8 * xq + 4 * hh];
-#pragma unroll
-          for (int x = 0; x < 4; ++x)
-            if (il < (int)((nd >> (8 * x)) & 255u)) sv[4 * xq + x] = -INFINITY;
-        }
-      }
-    };
-
-    if (part) {
-      f32x16 s0, s1;
-#pragma unroll
-      for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
-      bool exact = diag || vert || !have_max;
-      if (__builtin_expect(!exact, 1)) {
-        // ---- fast path.  Probabilities are taken relative to the running maximum of the
-        // PREVIOUS tiles (any reference value gives the same softmax; only overflow must be
-        // excluded), so the exponentials do not wait for this tile's maximum and are issued
-        // between the MFMAs:  S0 | S1 with exp(S0) | PV(0) with exp(S1) | PV(1).
-        // The true maximum is folded in after the tile.  If a score exceeds the reference by
-        // more than 2^64 the tile is redone on the exact path below.
-        // Operands are fetched from LDS two MFMAs ahead; the scheduling fences pin this
-        // hand-made interleaving.
-        const float c = a.scale_log2, mref = m_run;
-        constexpr int PF = 4;              // LDS fragments in flight ahead of the MFMAs
-        constexpr int NB = PF + 1;         // rotating fragment registers
-        bf16x8 kf[NB];
-#pragma unroll
-        for (int j = 0; j < PF; ++j) kf[j] = k_load(kb, j / DSTEPS, j % DSTEPS);
-#pragma unroll
-        for (int st = 0; st < DSTEPS; ++st) {
-          const int j = st + PF;
-          kf[j % NB] = k_load(kb, j / DSTEPS, j % DSTEPS);
-          s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st % NB], qreg[st], s0, 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        float mx = s0[0], ps = 0.f;
-        constexpr int EPS = 16 / DSTEPS;  // elements of the other half handled per MFMA step
-#pragma unroll
-        for (int st = 0; st < DSTEPS; ++st) {
-          const int j = DSTEPS + st + PF;
-          if (j < 2 * DSTEPS) kf[j % NB] = k_load(kb, 1, j - DSTEPS);
-          s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[(DSTEPS + st) % NB], qreg[st], s1, 0, 0, 0);
-#pragma unroll
-          for (int x = EPS * st; x < EPS * (st + 1); ++x) {
-            mx = fmaxf(mx, s0[x]);
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s0[x], c, -mref));
-            s0[x] = p;
-            ps += p;
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        mx = fmaxf(mx, block_max(s1));
-        exact = __any((mx * c > mref + 64.f) | !(ps < 3.0e38f));
-        if (__builtin_expect(!exact, 1)) {
-          constexpr int NPV = 2 * DB;            // PV MFMAs per 32-key half: (tt, db)
-          constexpr int EPV = 16 / NPV;          // exp(S1) elements per MFMA
-          constexpr int VPF = 3, VNB = VPF + 1;  // V fragments (two transposing reads each) in flight
-          bf16x8 vf[VNB], pb;
-#pragma unroll
-          for (int j = 0; j < VPF; ++j) vf[j] = v_load(vb, j / NPV, (j % NPV) / DB, j % DB);
-#pragma unroll
-          for (int i = 0; i < NPV; ++i) {
-            const int j = i + VPF;               // fragment fetched now: half j / NPV, tt, db
-            vf[j % VNB] = v_load(vb, j / NPV, (j % NPV) / DB, j % DB);
-            if (i % DB == 0) pb = to_bf16(s0, i / DB);
-            oacc[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % VNB], pb, oacc[i % DB], 0, 0, 0);
-#pragma unroll
-            for (int x = EPV * i; x < EPV * (i + 1); ++x) {
-              const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[x], c, -mref));
-              s1[x] = p;
-              ps += p;
-            }
-            __builtin_amdgcn_sched_barrier(0);
-          }
-#pragma unroll
-          for (int i = 0; i < NPV; ++i) {
-            const int j = NPV + i + VPF;
-            if (j < 2 * NPV) vf[j % VNB] = v_load(vb, 1, (j % NPV) / DB, j % DB);
-            if (i % DB == 0) pb = to_bf16(s1, i / DB);
-            oacc[i % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[(NPV + i) % VNB], pb, oacc[i % DB], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-          }
-          l_run += ps;
-          // fold this tile's maximum into the running maximum (rescales only when it grew)
-          const float mrow = fmaxf(mx, __shfl_xor(mx, 32)) * c;
-          if (__builtin_expect(__any(mrow > m_run), 0)) {
-            const float m_new = fmaxf(m_run, mrow);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-              for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
-          }
-        } else {
-#pragma unroll
-          for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
-        }
-      }
-      if (__builtin_expect(exact, 0)) {
-        // ---- exact path: masked tiles, the first tile(s) of a row block, overflow guard ----
-#pragma unroll
-        for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
-#pragma unroll
-        for (int st = 0; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
-        if (diag || vert) {
-          apply_mask(s0, 0);
-          apply_mask(s1, 1);
-        }
-        float mx = fmaxf(block_max(s0), block_max(s1));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * a.scale_log2);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
-        l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int x = 0; x < 16; ++x) oacc[db][x] *= alpha;
-        l_run += exp_block(s0, m_use);
-        l_run += exp_block(s1, m_use);
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 pb = to_bf16(s0, tt);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 0, tt, db);
-        }
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          const bf16x8 pb = to_bf16(s1, tt);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) pv_step(vb, pb, 1, tt, db);
-        }
-        have_max = !__any(m_run == -INFINITY);
-      }
-    }
-
+    vert = cur_kind == 1;
+  };
+  auto end_step = [&]() {
     int nn_kind = nxt_kind, nn_idx = nxt_idx, nn_mask = nxt_mask;
     if (nxt_kind != 2) advance(nn_kind, nn_idx, nn_mask);
     wait_copies();
@@ -493,6 +564,22 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     cur_kind = nxt_kind; cur_idx = nxt_idx; cur_mask = nxt_mask;
     nxt_kind = nn_kind; nxt_idx = nn_idx; nxt_mask = nn_mask;
     buf ^= 1;
+  };
+
+  for (;;) {
+    begin_step();
+    // steady state: runs of steps in which this wave multiplies tile i and folds in tile i - 1
+    while (__builtin_expect(pend && part && !(diag || vert || !have_max), 1)) {
+      if (__builtin_expect(!fused(kb, vbp), 0)) qk_exact(kb, diag, vert, apply_mask);
+      end_step();
+      begin_step();
+    }
+    if (pend) drain(vbp);
+    bool exact = diag || vert || !have_max;
+    if (part && !exact) exact = !qk_fast(kb);
+    if (__builtin_expect(part && exact, 0)) qk_exact(kb, diag, vert, apply_mask);
+    if (last) break;
+    end_step();
   }
 
   // ---- normalise and store ------------------------------------------------------------------
@@ -511,7 +598,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       }
     if (a.lse && hh == 0)
       a.lse[(int64_t)h * a.q_len + row] =
-          l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+          l_tot > 0.f ? (m_o + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
   }
 }
 
