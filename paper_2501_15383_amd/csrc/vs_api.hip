@@ -10,8 +10,9 @@ namespace {
 
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// the kernels keep a lane's byte offset inside a 64-token tile in 32 bits
 bool stride_ok(int64_t tok, int64_t head, int d) {
-  return tok >= d && head >= d && tok % 8 == 0 && head % 8 == 0;
+  return tok >= d && head >= d && tok % 8 == 0 && head % 8 == 0 && tok < (int64_t(1) << 23);
 }
 
 // shape / stride checks common to every entry point

@@ -65,9 +65,24 @@ constexpr int attn_lds_bytes() { return 4 * 64 * D * 2 + 2 * 64 * 4 + 8 * 64; }
 
 // Direct global -> LDS copy, 16 bytes per lane: lane L's bytes land at lds_addr + 16 L
 // (lds_addr is wave-uniform and goes through M0).  Completion is tracked by vmcnt.
-__device__ __forceinline__ void dma16_uniform_base(uint32_t lds_addr, const void* sbase, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+// N such copies from one scalar base with per-copy lane offsets; the LDS destinations are
+// lds_addr, lds_addr + step, ...  (M0 is read when a copy issues, so it can move on at once;
+// a write to M0 needs one wait state before the copy that uses it.)
+__device__ __forceinline__ void dma16x4(uint32_t lds_addr, const void* sbase, uint32_t o0, uint32_t o1,
+                                        uint32_t o2, uint32_t o3, uint32_t step) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\t"
+      "s_add_u32 m0, m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %5\n\t"
+      "s_add_u32 m0, m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %5\n\t"
+      "s_add_u32 m0, m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %5"
+      :: "s"(lds_addr), "v"(o0), "v"(o1), "v"(o2), "v"(o3), "s"(sbase), "s"(step) : "memory", "scc");
+}
+__device__ __forceinline__ void dma16x2(uint32_t lds_addr, const void* sbase, uint32_t o0, uint32_t o1,
+                                        uint32_t step) {
+  asm volatile(
+      "s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\t"
+      "s_add_u32 m0, m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
+      :: "s"(lds_addr), "v"(o0), "v"(o1), "s"(sbase), "s"(step) : "memory", "scc");
 }
 __device__ __forceinline__ void dma16_lane_ptr(uint32_t lds_addr, const void* ptr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
@@ -214,8 +229,13 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int kch = lc ^ ((r0 / R) % DCH);       // d-chunk it fetches for K (after the swizzle)
   const int vch = lc ^ ((((r0 / R) & 3) << 2) & (DCH - 1));  // ... and for V
   static_assert((WAVES * RPG / R) % DCH == 0 && (WAVES * RPG / R) % 4 == 0, "swizzle must not depend on e");
-  const uint32_t koff = (uint32_t)(r0 * a.k_stride_tok * 2 + kch * 16);
-  const uint32_t voff = (uint32_t)(r0 * a.v_stride_tok * 2 + vch * 16);
+  static_assert(GPW == 2 || GPW == 4, "copies of a tile per wave");
+  uint32_t koff[GPW], voff[GPW];  // byte offset of this lane's 16 bytes in copy e of a tile
+#pragma unroll
+  for (int e = 0; e < GPW; ++e) {
+    koff[e] = (uint32_t)((e * WAVES * RPG + r0) * a.k_stride_tok * 2 + kch * 16);
+    voff[e] = (uint32_t)((e * WAVES * RPG + r0) * a.v_stride_tok * 2 + vch * 16);
+  }
   auto issue_k = [&](int kind, int idx, int buf) {
     const uint32_t kdst = ks_addr + (uint32_t)(buf * TILE * 2 + wv * 1024);
     bool fast = false;
@@ -224,9 +244,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       if (__builtin_expect(j0 + 64 <= n_k, 1)) {  // whole block in range: uniform bases + one per-lane 32-bit offset
         fast = true;
         const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
-#pragma unroll
-        for (int e = 0; e < GPW; ++e)
-          dma16_uniform_base(kdst + e * WAVES * 1024, kt + (int64_t)e * WAVES * RPG * a.k_stride_tok * 2, koff);
+        if constexpr (GPW == 4) dma16x4(kdst, kt, koff[0], koff[1], koff[2], koff[3], WAVES * 1024);
+        else dma16x2(kdst, kt, koff[0], koff[1], WAVES * 1024);
       }
     }
     if (__builtin_expect(!fast, 0)) {
@@ -246,9 +265,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       if (__builtin_expect(j0 + 64 <= n_k, 1)) {
         fast = true;
         const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
-#pragma unroll
-        for (int e = 0; e < GPW; ++e)
-          dma16_uniform_base(vdst + e * WAVES * 1024, vt + (int64_t)e * WAVES * RPG * a.v_stride_tok * 2, voff);
+        if constexpr (GPW == 4) dma16x4(vdst, vt, voff[0], voff[1], voff[2], voff[3], WAVES * 1024);
+        else dma16x2(vdst, vt, voff[0], voff[1], WAVES * 1024);
       }
     }
     if (__builtin_expect(!fast, 0)) {
@@ -323,16 +341,15 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const float c = a.scale_log2;
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   typedef __attribute__((ext_vector_type(2))) float f32x2;
-  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
   constexpr float kTooLarge = 1.8446744e19f;  // 2^64: a probability above it means the reference is stale
   // probabilities of score pair (x, x + 1) of sv relative to ref, rounded to bf16 into operand
-  // P0 (x < 8) or P1; the row sum takes the rounded values, the numbers the PV contraction uses
+  // P0 (x < 8) or P1; the row sum takes the unrounded values (it also feeds the lse output)
   auto exp_pair = [&](const f32x16& sv, int x, float ref, bf16x8& P0, bf16x8& P1, float& ps) {
     f32x2 pf;
     pf[0] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x], c, -ref));
     pf[1] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[x + 1], c, -ref));
     const bf16x2 pk = __builtin_convertvector(pf, bf16x2);
-    ps = __builtin_amdgcn_fdot2_f32_bf16(pk, ones2, ps, false);
+    ps += pf[0] + pf[1];
     bf16x8& P = x < 8 ? P0 : P1;
     P[x & 7] = pk[0];
     P[(x & 7) + 1] = pk[1];
@@ -439,7 +456,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   //   C  3 NM / 2      the rest of PV(prev)                               | exp of keys 32..63
   // LDS operands are fetched PF MFMAs ahead; the scheduling fences pin the interleaving.
   // Returns false if a score outran the reference; the previous tile is folded in either way.
-  auto fused = [&](const __bf16* kb, const __bf16* vbp) -> bool {
+  auto fused = [&](const __bf16* kb, const __bf16* vbp, auto&& launch) -> bool {
     constexpr int PF = 3, NB = PF + 1;
     constexpr int NBQ = NM / 2;  // PV MFMAs mixed into phase B
     // MFMA n of the step: which operand it takes from LDS
@@ -456,6 +473,10 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     for (int x = 0; x < 16; ++x) { sa[x] = 0.f; sn[x] = 0.f; }
 #pragma unroll
     for (int j = 0; j < PF; ++j) fq[j] = frag(j);
+    // the first operands are on their way from LDS while the copies are launched
+    __builtin_amdgcn_sched_barrier(0);
+    launch();
+    __builtin_amdgcn_sched_barrier(0);
     bf16x8 q0, q1;  // the second half's operands replace pp[0], pp[1], which are spent by then
     float ps = 0.f;
     int xa = 0, xb = 0;  // next score pair of each half (compile-time after unrolling)
@@ -525,19 +546,15 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       }
     }
   };
-  // start of a step: launch the copies, find out whether this wave takes part in tile i and
-  // with which element mask.  A masked tile gives every key r of the tile a threshold need[r]:
+  // start of a step: find out whether this wave takes part in tile i and with which element
+  // mask.  A masked tile gives every key r of the tile a threshold need[r]:
   // row il of the query block may use it iff il >= need[r] (64 = never).  Slash tile on the
   // block's own diagonal: need[r] = r.  Vertical tile: 0 for a column of an earlier, uncovered
   // key block; the column's offset inside the block when it lies in the query block's own key
   // block; 64 when it is out of range, in a later block, or already covered by a computed
   // diagonal.
-  auto begin_step = [&]() {
+  auto classify = [&]() {
     last = cur_kind == 2;
-    if (!last) {
-      if (nxt_kind != 2) issue_k(nxt_kind, nxt_idx, buf ^ 1);
-      issue_v(cur_kind, cur_idx, buf);
-    }
     kb = Ks + buf * TILE;
     vbp = Vs + (buf ^ 1) * TILE;
     part = wave_valid && !last;
@@ -556,6 +573,13 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     }
     vert = cur_kind == 1;
   };
+  // copies of K(i + 1) and V(i) into the buffers that step i - 1 used last
+  auto launch_copies = [&]() {
+    if (!last) {
+      if (nxt_kind != 2) issue_k(nxt_kind, nxt_idx, buf ^ 1);
+      issue_v(cur_kind, cur_idx, buf);
+    }
+  };
   auto end_step = [&]() {
     int nn_kind = nxt_kind, nn_idx = nxt_idx, nn_mask = nxt_mask;
     if (nxt_kind != 2) advance(nn_kind, nn_idx, nn_mask);
@@ -567,13 +591,14 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   };
 
   for (;;) {
-    begin_step();
+    classify();
     // steady state: runs of steps in which this wave multiplies tile i and folds in tile i - 1
     while (__builtin_expect(pend && part && !(diag || vert || !have_max), 1)) {
-      if (__builtin_expect(!fused(kb, vbp), 0)) qk_exact(kb, diag, vert, apply_mask);
+      if (__builtin_expect(!fused(kb, vbp, launch_copies), 0)) qk_exact(kb, diag, vert, apply_mask);
       end_step();
-      begin_step();
+      classify();
     }
+    launch_copies();
     if (pend) drain(vbp);
     bool exact = diag || vert || !have_max;
     if (part && !exact) exact = !qk_fast(kb);
