@@ -477,6 +477,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     __builtin_amdgcn_sched_barrier(0);
     launch();
     __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(2);  // this wave's MFMA stream goes before the other workgroup's bookkeeping
     bf16x8 q0, q1;  // the second half's operands replace pp[0], pp[1], which are spent by then
     float ps = 0.f;
     int xa = 0, xb = 0;  // next score pair of each half (compile-time after unrolling)
@@ -500,6 +501,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    __builtin_amdgcn_s_setprio(0);
     l_run += pend_ps;
     pend = false;
     if (__builtin_expect(__any(!(ps < kTooLarge)), 0)) return false;

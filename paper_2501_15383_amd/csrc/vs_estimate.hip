@@ -8,8 +8,9 @@
 // tile is fetched from HBM once per sweep for all heads of the group and staged in LDS.
 //   sweep A  per-row running (max, sum) over the range -> partials -> k_estimate_combine -> lse
 //   sweep B  P = exp2(S * scale*log2e - lse2); column sums are stored directly (a column
-//            belongs to exactly one workgroup); diagonal sums are accumulated in an LDS strip
-//            private to the wave, then added to the zero-filled global array (at most two
+//            belongs to exactly one workgroup); the diagonal sums of every 32 x 32 block come
+//            from lane rotations, are collected in an LDS strip private to the wave, and the
+//            strip is added to the zero-filled global array at the end (at most two
 //            workgroups touch one offset, and x + y is commutative), so scores are
 //            run-to-run identical.
 // bf16 MFMA (32x32x16) with fp32 accumulation; sweep A uses the K Q^T orientation (a lane
@@ -157,15 +158,34 @@ __global__ __launch_bounds__(64 * NW) void k_estimate(const EstArgs a) {
               s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[ib][st], kf[st], s, 0, 0, 0);
             const int jl = 64 * tile + 32 * jb + (lane & 31);  // key index inside the range
             const int64_t j = ja + jl;
-            float colsum = 0.f;
+            // Diagonal sums of this 32 x 32 block without atomics.  Element x of a lane is
+            // query q = 8 (x/4) + 4 hh + (x%4) of the block against key t = lane % 32, on block
+            // diagonal e = q - t.  Rotating the 32-lane vector of element x by q lanes (inside
+            // each half-wave) puts e = -t (no wrap) or e = 32 - t (wrapped) into lane t for
+            // every x, so two accumulators per lane collect all 63 diagonals of the block.
+            float colsum = 0.f, dneg = 0.f, dpos = 0.f;
+            const int t4 = (lane & 31) + 4 * hh;
 #pragma unroll
             for (int x = 0; x < 16; ++x) {
-              const int i = 32 * ib + 8 * (x >> 2) + 4 * hh + (x & 3);
+              const int q0 = 8 * (x >> 2) + (x & 3);
+              const int i = 32 * ib + q0 + 4 * hh;
               float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -lse_r[ib][x]));
               if (need_mask && j > a.p0 + i) p = 0.f;
               colsum += p;
-              // offset o = p0 + i - j; strip index = i - jl + (kEstRange - 1) in [0, kEstRange + 62]
-              atomicAdd(&strip[wv * STRIP + i - jl + (kEstRange - 1)], p);
+              const int src = ((t4 + q0) & 31) | (lane & 32);
+              const float r = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, p)));
+              const bool wrapped = t4 + q0 >= 32;
+              dneg += wrapped ? 0.f : r;
+              dpos += wrapped ? r : 0.f;
+            }
+            dneg += __shfl_xor(dneg, 32);
+            dpos += __shfl_xor(dpos, 32);
+            // strip index of (query i, key jl) is i - jl + (kEstRange - 1); the strip is private
+            // to the wave and the 32 addresses of one update are distinct
+            if (hh == 0) {
+              float* sp = &strip[wv * STRIP + 32 * (ib - jb) - 64 * tile + (kEstRange - 1) - (lane & 31)];
+              sp[0] += dneg;
+              if ((lane & 31) != 0) sp[32] += dpos;
             }
             colacc += colsum;
           }
