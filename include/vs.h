@@ -49,7 +49,7 @@ enum {
 };
 
 /* which workspace size vs_workspace_bytes() reports */
-enum { VS_WS_ESTIMATE = 0, VS_WS_SELECT = 1, VS_WS_SPARSE = 2, VS_WS_DENSE = 3, VS_WS_CHUNK = 4 };
+enum { VS_WS_ESTIMATE = 0, VS_WS_SELECT = 1, VS_WS_SPARSE = 2, VS_WS_DENSE = 3, VS_WS_CHUNK = 4, VS_WS_COUNT_TILES = 5 };
 
 typedef struct vs_params {
   int32_t n_q_heads;       /* Hq                                                      */
@@ -147,6 +147,17 @@ int vs_prefill_chunk(const vs_params *p, const void *q, const void *k,
 int vs_count_tiles(const vs_params *p, const int32_t *v_idx, const int32_t *v_cnt,
                    const int32_t *s_idx, const int32_t *s_cnt, int64_t *tiles,
                    void *ws, size_t ws_bytes, void *stream);
+
+/* Host: process-wide tuning switches (no device call; not thread-safe against
+ * concurrent launches).  Returns VS_OK or VS_ERR_INVALID_ARG.
+ *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per key segment
+ *     of vs_sparse_attn_prefill, 0 = automatic.  Long contexts are cut into key
+ *     segments that are launched one after the other (K/V of a segment, all KV
+ *     heads, about 128 MiB) with a final sum over segments; results do not depend
+ *     on the launch order.  The choice changes VS_WS_SPARSE / VS_WS_CHUNK sizes,
+ *     so set it before asking for them. */
+enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0 };
+int vs_set_option(int which, int64_t value);
 
 #ifdef __cplusplus
 }

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libvs.so")
 
 VS_OK = 0
 VS_ERR_INVALID_ARG, VS_ERR_UNSUPPORTED, VS_ERR_WORKSPACE, VS_ERR_HIP = -1, -2, -3, -4
-VS_WS_ESTIMATE, VS_WS_SELECT, VS_WS_SPARSE, VS_WS_DENSE, VS_WS_CHUNK = range(5)
+VS_WS_ESTIMATE, VS_WS_SELECT, VS_WS_SPARSE, VS_WS_DENSE, VS_WS_CHUNK, VS_WS_COUNT_TILES = range(6)
+VS_OPT_ATTN_SEGMENT_BLOCKS = 0
 
 
 class VsParams(C.Structure):
@@ -70,6 +71,8 @@ def lib() -> C.CDLL:
         L.vs_dense_causal_prefill.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_prefill_chunk.restype = C.c_int
         L.vs_prefill_chunk.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_set_option.restype = C.c_int
+        L.vs_set_option.argtypes = [C.c_int, C.c_int64]
         L.vs_count_tiles.restype = C.c_int
         L.vs_count_tiles.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
@@ -77,7 +80,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
-           "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles"]
+           "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
+           "vs_set_option"]
 
 
 def status_string(status: int) -> str:
@@ -131,6 +135,11 @@ def _stream():
 def _check(rc, where):
     if rc != VS_OK:
         raise VsError(rc, where)
+
+
+def set_option(which: int, value: int) -> None:
+    """vs_set_option (process-wide tuning switch, e.g. VS_OPT_ATTN_SEGMENT_BLOCKS)."""
+    _check(lib().vs_set_option(int(which), C.c_int64(int(value))), "vs_set_option")
 
 
 def workspace_bytes(ck: Chunk, which: int) -> int:
@@ -259,7 +268,7 @@ def count_tiles(ck: Chunk, v_idx, v_cnt, s_idx, s_cnt):
     _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt)
     dev = v_idx.device
     tiles = torch.empty((ck.n_q_heads, 2), dtype=torch.int64, device=dev)
-    ws, n = _ws(ck, VS_WS_SPARSE, dev)
+    ws, n = _ws(ck, VS_WS_COUNT_TILES, dev)
     p = ck.params()
     _check(lib().vs_count_tiles(C.byref(p), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx), _ptr(s_cnt), _ptr(tiles),
                                 _ptr(ws), n, _stream()), "vs_count_tiles")

@@ -44,7 +44,7 @@ int check_ws(const void* ws, size_t have, size_t need) {
   return VS_OK;
 }
 
-size_t sparse_ws_bytes(const vs_params& p, bool dense) { return blocklist_bytes(p, dense); }
+size_t sparse_ws_bytes(const vs_params& p, bool dense) { return blocklist_bytes(p, dense) + attn_partial_bytes(p, dense); }
 
 // layout of the VS_WS_CHUNK workspace
 struct ChunkWs {
@@ -78,13 +78,14 @@ using namespace vs;
 extern "C" {
 
 size_t vs_workspace_bytes(const vs_params* p, int which) {
-  if (check_params(p, which == VS_WS_SELECT || which == VS_WS_SPARSE || which == VS_WS_CHUNK) != VS_OK) return 0;
+  if (check_params(p, which == VS_WS_SELECT || which == VS_WS_SPARSE || which == VS_WS_CHUNK || which == VS_WS_COUNT_TILES) != VS_OK) return 0;
   switch (which) {
     case VS_WS_ESTIMATE: return estimate_ws_bytes(*p);
     case VS_WS_SELECT: return select_ws_bytes(*p);
     case VS_WS_SPARSE: return sparse_ws_bytes(*p, false);
     case VS_WS_DENSE: return sparse_ws_bytes(*p, true);
     case VS_WS_CHUNK: return chunk_layout(*p).total;
+    case VS_WS_COUNT_TILES: return blocklist_bytes(*p, false);
     default: return 0;
   }
 }
@@ -97,6 +98,16 @@ const char* vs_status_string(int status) {
     case VS_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case VS_ERR_HIP: return "HIP runtime error at launch";
     default: return "unknown status";
+  }
+}
+
+int vs_set_option(int which, int64_t value) {
+  switch (which) {
+    case VS_OPT_ATTN_SEGMENT_BLOCKS:
+      if (value < 0 || value > (int64_t)INT32_MAX) return VS_ERR_INVALID_ARG;
+      set_attn_segment_blocks((int)value);
+      return VS_OK;
+    default: return VS_ERR_INVALID_ARG;
   }
 }
 
@@ -142,7 +153,8 @@ int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, con
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_build_blocklist(*p, s_idx, s_cnt, false, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, k, v, v_idx, v_cnt, false, bl, out, lse, st));
+  return hip_status(launch_attention(*p, q, k, v, v_idx, v_cnt, false, bl, out, lse,
+                                     (char*)ws + blocklist_bytes(*p, false), st));
 }
 
 int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, const void* v,
@@ -157,7 +169,8 @@ int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, co
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_build_blocklist(*p, nullptr, nullptr, true, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, k, v, nullptr, nullptr, true, bl, out, lse, st));
+  return hip_status(launch_attention(*p, q, k, v, nullptr, nullptr, true, bl, out, lse,
+                                     (char*)ws + blocklist_bytes(*p, true), st));
 }
 
 int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const void* v, void* out,
@@ -191,7 +204,7 @@ int vs_count_tiles(const vs_params* p, const int32_t* v_idx, const int32_t* v_cn
   int rc = check_params(p, true);
   if (rc != VS_OK) return rc;
   if (!v_idx || !v_cnt || !s_idx || !s_cnt || !tiles) return VS_ERR_INVALID_ARG;
-  rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
+  rc = check_ws(ws, ws_bytes, blocklist_bytes(*p, false));
   if (rc != VS_OK) return rc;
   const BlockList bl = blocklist_layout(*p, false, ws);
   hipStream_t st = (hipStream_t)stream;
