@@ -79,6 +79,8 @@ def main():
     ap.add_argument("--workload", default="7b_1m")
     ap.add_argument("--chunk-index", type=int, default=-1, help="which chunk of the context (-1 = last)")
     ap.add_argument("--n-ctx", type=int, default=0, help="override the context length (tokens)")
+    ap.add_argument("--segment-blocks", type=int, default=0,
+                    help="64-key blocks per key segment of the sparse launch (0 = the library's choice)")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -94,6 +96,7 @@ def main():
     import torch
 
     import paper_2501_15383_amd as vs
+    vs.set_option(vs.VS_OPT_ATTN_SEGMENT_BLOCKS, args.segment_blocks)
     import vsgen
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     vs.lib()   # fail loudly if the HIP library is not built

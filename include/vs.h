@@ -153,7 +153,7 @@ int vs_count_tiles(const vs_params *p, const int32_t *v_idx, const int32_t *v_cn
  *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per key segment
  *     of vs_sparse_attn_prefill, 0 = automatic.  Long contexts are cut into key
  *     segments that are launched one after the other (K/V of a segment, all KV
- *     heads, about 128 MiB) with a final sum over segments; results do not depend
+ *     heads, at most 80 MiB) with a final sum over segments; results do not depend
  *     on the launch order.  The choice changes VS_WS_SPARSE / VS_WS_CHUNK sizes,
  *     so set it before asking for them. */
 enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0 };

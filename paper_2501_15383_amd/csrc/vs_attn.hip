@@ -845,7 +845,8 @@ hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, cons
 // Key-range split of the sparse launch.  Workgroups that share a KV head drift apart on long
 // contexts and would each pull their own copy of K/V through the memory fabric; cutting the
 // key range into segments that are launched one after the other keeps the working set of the
-// whole chip (segment x all KV heads, K and V) near 128 MiB.  0 = choose automatically.
+// whole chip (segment x all KV heads, K and V) at or below 80 MiB (measured best at the 7B
+// shape: 512 blocks).  0 = choose automatically.
 static int g_segment_blocks = 0;
 void set_attn_segment_blocks(int blocks) { g_segment_blocks = blocks < 0 ? 0 : blocks; }
 
@@ -858,7 +859,7 @@ void attn_segments(const vs_params& p, bool dense, int* seg_blocks, int* n_seg) 
     } else {
       const int64_t per_block = (int64_t)kBlock * p.n_kv_heads * p.head_dim * 2 * 2;  // K and V, all KV heads
       sb = 1;
-      while (sb * 2 * per_block <= (int64_t(160) << 20)) sb *= 2;
+      while (sb * 2 * per_block <= (int64_t(80) << 20)) sb *= 2;
     }
   }
   if (sb >= n_blk) { *seg_blocks = (int)n_blk; *n_seg = 1; return; }
