@@ -150,12 +150,13 @@ int vs_count_tiles(const vs_params *p, const int32_t *v_idx, const int32_t *v_cn
 
 /* Host: process-wide tuning switches (no device call; not thread-safe against
  * concurrent launches).  Returns VS_OK or VS_ERR_INVALID_ARG.
- *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per key segment
- *     of vs_sparse_attn_prefill, 0 = automatic.  Long contexts are cut into key
- *     segments that are launched one after the other (K/V of a segment, all KV
- *     heads, at most 80 MiB) with a final sum over segments; results do not depend
- *     on the launch order.  The choice changes VS_WS_SPARSE / VS_WS_CHUNK sizes,
- *     so set it before asking for them. */
+ *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per sync segment of the
+ *     attention launches, 0 = automatic.  The attention kernels are persistent;
+ *     workgroups that walk the same head keep within two sync segments of each
+ *     other (bounded waits on counters in the workspace) so that their K/V
+ *     blocks are shared through the L2.  Only the timing depends on it.  The
+ *     choice changes VS_WS_SPARSE / VS_WS_DENSE / VS_WS_CHUNK sizes, so set it
+ *     before asking for them. */
 enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0 };
 int vs_set_option(int which, int64_t value);
 

@@ -44,7 +44,7 @@ int check_ws(const void* ws, size_t have, size_t need) {
   return VS_OK;
 }
 
-size_t sparse_ws_bytes(const vs_params& p, bool dense) { return blocklist_bytes(p, dense) + attn_partial_bytes(p, dense); }
+size_t sparse_ws_bytes(const vs_params& p, bool dense) { return blocklist_bytes(p, dense) + attn_sync_bytes(p); }
 
 // layout of the VS_WS_CHUNK workspace
 struct ChunkWs {

@@ -53,11 +53,14 @@ struct AttnArgs {
   int32_t n_qtiles;
   int64_t q_len, q_start;
   float scale_log2;  // softmax_scale * log2(e)
-  // key-range split: segment s covers key blocks [s * seg_blocks, (s + 1) * seg_blocks); with
-  // n_seg > 1 every (query tile, head, segment) workgroup writes unnormalised partial results
-  int32_t n_seg, seg_blocks, blocks_per_seg;
-  float* part_o;   // [n_seg][n_q_heads][q_len][D] fp32
-  float* part_ml;  // [n_seg][n_q_heads][q_len][2]  (reference m, row sum l), log2 domain
+  // persistent launch: n_wg workgroups, workgroup b is member b / 8 of group b % 8 (the groups
+  // follow the round-robin of workgroups over the 8 XCDs); in round r group g works on
+  // group-round k = 8 r + g = (chunk of `members` consecutive query tiles, head), one tile each
+  int32_t n_wg, members, n_chunks;
+  // pace keeping: arrive[g][s] counts the members of group g that are done with key blocks
+  // [s * sync_blocks, (s + 1) * sync_blocks) over all rounds so far
+  int32_t sync_blocks, n_sync;
+  uint32_t* arrive;
 };
 
 __device__ __forceinline__ bool bm_test(const uint32_t* bm, int i) {
@@ -122,27 +125,58 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   uint8_t* const need_s = (uint8_t*)(vidx_s + 2 * 64);  // [waves][64], private to each wave
   const uint32_t ks_addr = lds_address(Ks), vs_addr = lds_address(Vs);
 
-  // ---- which (query tile, head) -------------------------------------------------------
-  // workgroups of one key segment are launched together (segment-major), so that at any time
-  // the chip works on a key range small enough for the last-level cache
-  const int seg = a.n_seg > 1 ? (int)(blockIdx.x / (unsigned)a.blocks_per_seg) : 0;
-  const int bis = a.n_seg > 1 ? (int)(blockIdx.x % (unsigned)a.blocks_per_seg) : (int)blockIdx.x;
-  const int xcd = bis & 7, slot = bis >> 3;
-  const int gi = (slot / a.group) * 8 + xcd, hin = slot % a.group;
-  if (gi >= a.n_qtiles * a.n_kv_heads) return;
-  const int qt = a.n_qtiles - 1 - gi / a.n_kv_heads;
-  const int g = gi % a.n_kv_heads, h = g * a.group + hin;
-
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform
   const int t = wv >> 1;                          // query block of this wave inside the tile
   const int il = ((wv & 1) << 5) + (lane & 31);   // row inside the query block
   const int hh = lane >> 5;
+  const int64_t n_k = a.q_start + a.q_len;
+
+  // ---- persistent workgroup: one (query tile, head) per round ------------------------------
+  // The `members` workgroups of a group take consecutive query tiles of ONE head, so they walk
+  // the same entry list, shifted by two key blocks per tile, at the same pace; the arrive
+  // counters below keep the group inside a window of a few sync segments, small enough for
+  // the XCD's L2, so that a K/V block is fetched from memory once per group and round.
+  // Waiting is bounded and only shapes the timing: results never depend on it.
+  const int grp = blockIdx.x & 7, member = blockIdx.x >> 3;
+  const int n_gr = a.n_chunks * a.n_q_heads;      // group-rounds: latest chunks first, heads inside
+  uint32_t* const arr = a.arrive + (int64_t)grp * a.n_sync;
+  const int s_glob_top = (int)((n_k - 1) / 64) / a.sync_blocks;  // highest sync segment of the chunk
+  for (int rnd = 0; rnd * 8 + grp < n_gr; ++rnd) {
+  const int gr = rnd * 8 + grp;
+  const int chunk = a.n_chunks - 1 - gr / a.n_q_heads, h = gr % a.n_q_heads;
+  const int g = h / a.group;
+  const int qt = chunk * a.members + (a.members - 1 - member);
+  const uint32_t expected = (uint32_t)(rnd + 1) * (uint32_t)a.members;
+  // marks key segments seg_done - 1, ..., s_new done for this member, then holds the workgroup
+  // back (wave 0 polls, the others meet it at the step barrier) until the whole group is done
+  // with segment s_new + 2
+  int seg_done = s_glob_top + 1;
+  bool patient = true;  // a wait that ran out (group not co-resident?) ends the waiting for this tile
+  auto enter_segment = [&](int s_new, bool wait) {
+    if (s_new >= seg_done - 1) return;  // still in the segment entered last
+    if (wv == 0) {
+      for (int sg = seg_done - 1 - lane; sg > s_new; sg -= 64) atomicAdd(&arr[sg], 1u);
+      if (wait && patient && s_new + 2 <= s_glob_top) {
+        int spins = 0;
+        while (__hip_atomic_load(&arr[s_new + 2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < expected &&
+               spins < 2048) {
+          __builtin_amdgcn_s_sleep(16);
+          ++spins;
+        }
+        patient = spins < 2048;
+      }
+    }
+    seg_done = s_new + 1;
+  };
+  if (qt >= a.n_qtiles) {  // no tile for this member in this round
+    enter_segment(-1, false);
+    continue;
+  }
   const int64_t row0 = (int64_t)qt * (64 * NQB);
   const int64_t row = row0 + 64 * t + il;
   const int m0 = (int)(a.q_start / 64) + qt * NQB;  // absolute index of query block t = 0
   const bool wave_valid = row0 + 64 * t + ((wv & 1) << 5) < a.q_len;
-  const int64_t n_k = a.q_start + a.q_len;
   const int64_t rows_in_tile = (a.q_len - row0) < 64 * NQB ? (a.q_len - row0) : 64 * NQB;
   const int64_t last_pos = a.q_start + row0 + rows_in_tile - 1;
 
@@ -150,17 +184,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const uint32_t* ent_h = a.ent + (int64_t)h * a.ent_stride;
   const int32_t* vidx_h = a.v_idx ? a.v_idx + (int64_t)h * a.v_budget : nullptr;
   const int vcnt = a.v_idx ? __builtin_amdgcn_readfirstlane(a.v_cnt[h]) : 0;
-  const int n_vt = seg == 0 ? (vcnt + 63) >> 6 : 0;  // the gathered columns go with segment 0
-  // entry cc stands for key block m0 + (NQB - 1) - cc; this workgroup walks the entries whose
-  // key block lies in its segment (all of them when the key range is not split)
-  int cc_first = 0, cc_last = m0 + NQB - 1;  // cc = c + NQB - 1, c <= m0
-  if (a.n_seg > 1) {
-    const int n_top = m0 + NQB - 1;
-    if (seg * a.seg_blocks > n_top) return;  // segment entirely above the tile's diagonal
-    const int lo = n_top - ((seg + 1) * a.seg_blocks - 1), hi = n_top - seg * a.seg_blocks;
-    cc_first = lo > 0 ? lo : 0;
-    cc_last = hi < cc_last ? hi : cc_last;
-  }
+  const int n_vt = (vcnt + 63) >> 6;
+  const int cc_last = m0 + NQB - 1;  // entry cc stands for key block m0 + (NQB - 1) - cc >= 0
 
   const __bf16* kbase = a.k + (int64_t)g * a.k_stride_head;
   const __bf16* vbase = a.v + (int64_t)g * a.v_stride_head;
@@ -202,34 +227,25 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // ---- tile iterator (uniform over the workgroup, kept in scalar registers) -----------------
   // kind 0: slash tile, idx = cc, mask = query blocks that use it; kind 1: vertical tile,
   // idx = vt; kind 2: end.  Entries are fetched 64 at a time (one per lane), one batch ahead.
-  int e_first = 0;  // index of the first entry with cc >= cc_first (the list ascends)
-  if (cc_first > 0) {
-    int lo = 0, span = (int)a.ent_len;
-    while (span > 64) {  // 64-ary search, one sample per lane
-      const int step = (span + 63) >> 6;
-      int at = lo + lane * step;
-      at = at < (int)a.ent_len - 1 ? at : (int)a.ent_len - 1;
-      const int below = __popcll(__ballot((int)(ent_h[at] >> 4) < cc_first));
-      lo += (below > 0 ? below - 1 : 0) * step;
-      span = step;
-    }
-    e_first = lo + __popcll(__ballot((int)(ent_h[lo + lane] >> 4) < cc_first));
-    e_first = __builtin_amdgcn_readfirstlane(e_first);
-  }
-  uint32_t ecache = ent_h[(e_first & ~63) + lane], ecache_nx = ent_h[(e_first & ~63) + 64 + lane];
-  int ei = e_first - 1;
+  uint32_t ecache = ent_h[lane], ecache_nx = ent_h[64 + lane];
+  int ei = -1;
   auto advance = [&](int& kind, int& idx, int& mask) {
     int k2 = kind, i2 = idx, m2 = 0;
     if (k2 == 0) {
       ++ei;
-      if (__builtin_expect((ei & 63) == 0 && ei != e_first, 0)) {
+      if (__builtin_expect((ei & 63) == 0 && ei > 0, 0)) {
         ecache = ecache_nx;
         ecache_nx = ent_h[(ei & ~63) + 64 + lane];
       }
       const uint32_t e = __builtin_amdgcn_readlane(ecache, ei & 63);
       const int cc = (int)(e >> 4);
-      if (cc <= cc_last) { i2 = cc; m2 = (int)(e & 15u); }
-      else { k2 = 1; i2 = -1; }
+      if (cc <= cc_last) {
+        i2 = cc; m2 = (int)(e & 15u);
+        enter_segment((cc_last - cc) / a.sync_blocks, true);
+      } else {
+        k2 = 1; i2 = -1;
+        enter_segment(-1, false);  // the slash walk is over
+      }
     }
     if (k2 == 1) {
       const int vt = i2 + 1;
@@ -642,28 +658,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     end_step();
   }
 
-  // ---- normalise and store, or hand the unnormalised partial result to the combine kernel ------
+  // ---- normalise and store ------------------------------------------------------------------
   const float l_tot = l_run + __shfl_xor(l_run, 32);
-  if (a.n_seg > 1) {
-    if (row < a.q_len) {
-      const int64_t pr = ((int64_t)seg * a.n_q_heads + h) * a.q_len + row;
-      float* op = a.part_o + pr * D;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          f32x4 o4;
-#pragma unroll
-          for (int x = 0; x < 4; ++x) o4[x] = oacc[db][4 * vq + x];
-          *(f32x4*)(op + 32 * db + 8 * vq + 4 * hh) = o4;
-        }
-      if (hh == 0) {
-        a.part_ml[2 * pr] = m_o;
-        a.part_ml[2 * pr + 1] = l_tot;
-      }
-    }
-    return;
-  }
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   if (row < a.q_len) {
     __bf16* op = a.out + row * a.o_stride_tok + (int64_t)h * a.o_stride_head;
@@ -680,41 +676,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       a.lse[(int64_t)h * a.q_len + row] =
           l_tot > 0.f ? (m_o + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
   }
-}
-
-// Sum of the per-segment partial results of one row: out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M)
-// with M = max_s m_s, over the segments at or below the row's query tile (the others were
-// never written).  One thread per (row, 4 output elements); fixed order, so deterministic.
-template <int D, int NQB>
-__global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
-  constexpr int QPR = D / 4;            // threads per row
-  constexpr int RPB = 256 / QPR;        // rows per workgroup
-  const int h = blockIdx.y;
-  const int64_t row = (int64_t)blockIdx.x * RPB + threadIdx.x / QPR;
-  const int dq = threadIdx.x % QPR;
-  if (row >= a.q_len) return;
-  const int n_top = (int)(a.q_start / 64) + (int)(row / (64 * NQB)) * NQB + NQB - 1;
-  int s_top = n_top / a.seg_blocks;
-  if (s_top > a.n_seg - 1) s_top = a.n_seg - 1;
-  const int64_t seg_stride = (int64_t)a.n_q_heads * a.q_len;
-  const int64_t pr0 = (int64_t)h * a.q_len + row;
-  float M = -INFINITY;
-  for (int sg = 0; sg <= s_top; ++sg) M = fmaxf(M, a.part_ml[2 * (pr0 + sg * seg_stride)]);
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  float L = 0.f;
-  for (int sg = 0; sg <= s_top; ++sg) {
-    const int64_t pr = pr0 + sg * seg_stride;
-    const float m = a.part_ml[2 * pr], l = a.part_ml[2 * pr + 1];
-    const float w = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
-    L += l * w;
-    const f32x4 o = *(const f32x4*)(a.part_o + pr * D + 4 * dq);
-    acc += o * w;
-  }
-  const float inv = L > 0.f ? 1.0f / L : 0.f;
-  __bf16* op = a.out + row * a.o_stride_tok + (int64_t)h * a.o_stride_head + 4 * dq;
-  *(bf16x4*)op = __builtin_convertvector(acc * inv, bf16x4);
-  if (a.lse && dq == 0)
-    a.lse[(int64_t)h * a.q_len + row] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
+  enter_segment(-1, false);  // (a tile whose walk ended early has marked nothing yet)
+  __syncthreads();           // the LDS tiles are reused by the next round
+  }  // rounds
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -842,43 +806,32 @@ hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, cons
   return hipGetLastError();
 }
 
-// Key-range split of the sparse launch.  Workgroups that share a KV head drift apart on long
-// contexts and would each pull their own copy of K/V through the memory fabric; cutting the
-// key range into segments that are launched one after the other keeps the working set of the
-// whole chip (segment x all KV heads, K and V) at or below 80 MiB (measured best at the 7B
-// shape: 512 blocks).  0 = choose automatically.
-static int g_segment_blocks = 0;
-void set_attn_segment_blocks(int blocks) { g_segment_blocks = blocks < 0 ? 0 : blocks; }
-
-void attn_segments(const vs_params& p, bool dense, int* seg_blocks, int* n_seg) {
+// Pace keeping of the persistent launch: key blocks per sync segment.  The members of a group
+// (one XCD) may be at most two segments apart, so three segments of K and V (64 KiB per block
+// at D = 128) should fit the 4 MiB L2 of an XCD next to Q and the block lists.  0 = automatic.
+static int g_sync_blocks = 0;
+void set_attn_segment_blocks(int blocks) { g_sync_blocks = blocks < 0 ? 0 : blocks; }
+static int attn_sync_blocks(const vs_params& p) {
+  if (g_sync_blocks > 0) return g_sync_blocks;
+  const int per_block = kBlock * p.head_dim * 2 * 2;  // K and V of one KV head
+  int sb = 1;
+  while (sb * 2 * 3 * per_block <= (3 << 20)) sb *= 2;
+  return sb;
+}
+size_t attn_sync_bytes(const vs_params& p) {
   const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
-  int64_t sb = n_blk;
-  if (!dense) {
-    if (g_segment_blocks > 0) {
-      sb = g_segment_blocks;
-    } else {
-      const int64_t per_block = (int64_t)kBlock * p.n_kv_heads * p.head_dim * 2 * 2;  // K and V, all KV heads
-      sb = 1;
-      while (sb * 2 * per_block <= (int64_t(80) << 20)) sb *= 2;
-    }
-  }
-  if (sb >= n_blk) { *seg_blocks = (int)n_blk; *n_seg = 1; return; }
-  *seg_blocks = (int)sb;
-  *n_seg = (int)ceil_div(n_blk, sb);
+  return align_up((size_t)8 * (size_t)ceil_div(n_blk, attn_sync_blocks(p)) * sizeof(uint32_t), 256);
 }
 
-size_t attn_partial_bytes(const vs_params& p, bool dense) {
-  int sb, ns;
-  attn_segments(p, dense, &sb, &ns);
-  if (ns == 1) return 0;
-  const size_t rows = (size_t)ns * p.n_q_heads * (size_t)p.q_len;
-  return align_up(rows * p.head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256);
+__global__ __launch_bounds__(256) void k_fill_zero_u32(uint32_t* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
 hipError_t launch_attention(const vs_params& p, const void* q, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
-                            const BlockList& bl, void* out, float* lse, void* part_ws, hipStream_t st) {
+                            const BlockList& bl, void* out, float* lse, void* sync_ws, hipStream_t st) {
   constexpr int NQB = kAttnQBlocks;
+  if (!sync_ws) return hipErrorInvalidValue;
   AttnArgs a;
   a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v;
   a.out = (__bf16*)out; a.lse = lse;
@@ -896,19 +849,26 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
   a.n_qtiles = (int)ceil_div(p.q_len, 64 * NQB);
   a.q_len = p.q_len; a.q_start = p.q_start;
   a.scale_log2 = p.softmax_scale * kLog2e;
-  const int64_t groups = (int64_t)a.n_qtiles * p.n_kv_heads;
-  const int64_t blocks = ceil_div(groups, 8) * 8 * a.group;
-  int sb, ns;
-  attn_segments(p, dense, &sb, &ns);
-  a.n_seg = ns; a.seg_blocks = sb; a.blocks_per_seg = (int32_t)blocks;
-  a.part_o = nullptr; a.part_ml = nullptr;
-  if (ns > 1) {
-    if (!part_ws) return hipErrorInvalidValue;
-    const size_t rows = (size_t)ns * p.n_q_heads * (size_t)p.q_len;
-    a.part_o = (float*)part_ws;
-    a.part_ml = (float*)((char*)part_ws + align_up(rows * p.head_dim * sizeof(float), 256));
+  // two workgroups fit a compute unit; one persistent workgroup per slot, in 8 groups
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
+      return hipErrorInvalidDevice;
+    n_cu = cu;
   }
-  if (blocks * ns > (int64_t)0x7FFFFFFF) return hipErrorInvalidValue;
+  int members = (2 * n_cu) / 8;
+  if (members < 1) members = 1;
+  if (members > a.n_qtiles) members = a.n_qtiles;  // short chunks: fewer, not idle, workgroups
+  a.members = members;
+  a.n_wg = 8 * members;
+  a.n_chunks = (int)ceil_div(a.n_qtiles, members);
+  a.sync_blocks = attn_sync_blocks(p);
+  a.n_sync = (int)ceil_div(ceil_div(p.q_start + p.q_len, kBlock), a.sync_blocks);
+  a.arrive = (uint32_t*)sync_ws;
+  hipLaunchKernelGGL(k_fill_zero_u32, dim3((unsigned)ceil_div(8 * (int64_t)a.n_sync, 256)), dim3(256), 0, st,
+                     a.arrive, 8 * (int64_t)a.n_sync);
   // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel
   static bool attr_set = false;
   if (!attr_set) {
@@ -920,16 +880,10 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid((unsigned)(blocks * ns));
-  if (p.head_dim == 128) {
-    hipLaunchKernelGGL((k_attention<128, NQB>), grid, dim3(128 * NQB), attn_lds_bytes<128>(), st, a);
-    if (ns > 1)
-      hipLaunchKernelGGL((k_attn_combine<128, NQB>), dim3((unsigned)ceil_div(p.q_len, 8), p.n_q_heads), dim3(256), 0, st, a);
-  } else {
-    hipLaunchKernelGGL((k_attention<64, NQB>), grid, dim3(128 * NQB), attn_lds_bytes<64>(), st, a);
-    if (ns > 1)
-      hipLaunchKernelGGL((k_attn_combine<64, NQB>), dim3((unsigned)ceil_div(p.q_len, 16), p.n_q_heads), dim3(256), 0, st, a);
-  }
+  if (p.head_dim == 128)
+    hipLaunchKernelGGL((k_attention<128, NQB>), dim3((unsigned)a.n_wg), dim3(128 * NQB), attn_lds_bytes<128>(), st, a);
+  else
+    hipLaunchKernelGGL((k_attention<64, NQB>), dim3((unsigned)a.n_wg), dim3(128 * NQB), attn_lds_bytes<64>(), st, a);
   return hipGetLastError();
 }
 

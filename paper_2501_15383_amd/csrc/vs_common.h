@@ -61,12 +61,11 @@ static inline BlockList blocklist_layout(const vs_params& p, bool dense, void* w
 // ---- launchers (defined in the .hip files; all enqueue on `st`, return hipError_t) ------
 hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, const int32_t* s_cnt,
                                   bool dense, const BlockList& bl, hipStream_t st);
-// part_ws: attn_partial_bytes(p, dense) bytes (may be null when that is 0)
+// sync_ws: attn_sync_bytes(p) bytes of counters (zero-filled by the launch itself)
 hipError_t launch_attention(const vs_params& p, const void* q, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
-                            const BlockList& bl, void* out, float* lse, void* part_ws, hipStream_t st);
-size_t attn_partial_bytes(const vs_params& p, bool dense);
-void attn_segments(const vs_params& p, bool dense, int* seg_blocks, int* n_seg);
+                            const BlockList& bl, void* out, float* lse, void* sync_ws, hipStream_t st);
+size_t attn_sync_bytes(const vs_params& p);
 void set_attn_segment_blocks(int blocks);
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,
                               const BlockList& bl, int64_t* tiles, hipStream_t st);
