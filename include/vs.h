@@ -148,6 +148,35 @@ int vs_count_tiles(const vs_params *p, const int32_t *v_idx, const int32_t *v_cn
                    const int32_t *s_idx, const int32_t *s_cnt, int64_t *tiles,
                    void *ws, size_t ws_bytes, void *stream);
 
+/* Step a2 with one budget pair per head (sec. 5.2: the configuration, i.e. the
+ * number of vertical and slash lines, is searched per attention head).
+ *   v_budget_h, s_budget_h: device int32 [Hq], clamped to 1 .. p->vertical_budget
+ *   / p->slash_budget, which stay the row lengths of v_idx / s_idx (rows padded
+ *   with -1).  Everything else as vs_select. */
+int vs_select_heads(const vs_params *p, const float *vscore, const float *sscore,
+                    const int32_t *v_budget_h, const int32_t *s_budget_h,
+                    int32_t *v_idx, int32_t *v_cnt, int32_t *s_idx, int32_t *s_cnt,
+                    void *ws, size_t ws_bytes, void *stream);
+
+/* Attention recall of every head over the chunk (sec. 5.2 "Sparsity refinement":
+ * Attention_Recall = exp(softmax_lse_sparse - softmax_lse_full) per query; here
+ * its mean over the chunk's rows, a row without selected keys counting 0).
+ *   lse_sparse, lse_full: device fp32 [Hq][C] as written by the attention calls
+ *   recall: device fp32 [Hq].  Deterministic (fixed reduction order). */
+int vs_attention_recall(const vs_params *p, const float *lse_sparse,
+                        const float *lse_full, float *recall, void *stream);
+
+/* One pass of the sparsity refinement over the heads (sec. 5.2, Algorithm 1):
+ * a head whose recall is below `threshold` gets add_vertical / add_slash more
+ * lines, up to p->vertical_budget / p->slash_budget.
+ *   recall: device fp32 [Hq]; v_budget_h, s_budget_h: device int32 [Hq], updated
+ *   in place; changed: optional device int32, number of heads whose budgets grew.
+ * The calibration data, the threshold and the step sizes are the caller's: the
+ * paper does not print them. */
+int vs_refine_step(const vs_params *p, const float *recall, float threshold,
+                   int32_t add_vertical, int32_t add_slash, int32_t *v_budget_h,
+                   int32_t *s_budget_h, int32_t *changed, void *stream);
+
 /* Host: process-wide tuning switches (no device call; not thread-safe against
  * concurrent launches).  Returns VS_OK or VS_ERR_INVALID_ARG.
  *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per sync segment of the

@@ -109,6 +109,42 @@ def attention_recall(lse_sparse, lse_full):
     return np.exp(np.asarray(lse_sparse, np.float64) - np.asarray(lse_full, np.float64))
 
 
+def recall_mean(lse_sparse, lse_full):
+    """Per-head attention recall of a chunk: mean over rows of exp(lse_sparse - lse_full).
+    lse arrays [nh][rows] -> [nh]."""
+    a = np.ascontiguousarray(lse_sparse, np.float64); b = np.ascontiguousarray(lse_full, np.float64)
+    assert a.shape == b.shape and a.ndim == 2
+    L = lib()
+    L.vso_recall_mean.restype = C.c_double
+    return np.array([L.vso_recall_mean(_p(a[h], C.c_double), _p(b[h], C.c_double), C.c_int64(a.shape[1]))
+                     for h in range(a.shape[0])])
+
+
+def refine_step(recall, threshold, dv, ds, v_max, s_max, v_budget, s_budget):
+    """One pass of the sparsity refinement over the heads.  Returns (v_budget, s_budget, changed)."""
+    recall = np.ascontiguousarray(recall, np.float64)
+    vb = np.array(v_budget, np.int32); sb = np.array(s_budget, np.int32)
+    L = lib()
+    L.vso_refine_step.restype = C.c_int
+    ch = L.vso_refine_step(C.c_int(len(recall)), _p(recall, C.c_double), C.c_double(threshold), C.c_int32(dv),
+                           C.c_int32(ds), C.c_int32(v_max), C.c_int32(s_max), _p(vb, C.c_int32), _p(sb, C.c_int32))
+    return vb, sb, int(ch)
+
+
+def select_heads(pb: Problem, vscore, sscore, v_budget, s_budget):
+    """Step 2 with one (vertical, slash) budget pair per head; rows padded with -1 to the
+    budgets of `pb` (the maxima)."""
+    nh = len(v_budget)
+    v_idx = np.full((nh, pb.vertical_budget), -1, np.int32); v_cnt = np.zeros(nh, np.int32)
+    s_idx = np.full((nh, pb.slash_budget), -1, np.int32); s_cnt = np.zeros(nh, np.int32)
+    for h in range(nh):
+        assert 1 <= v_budget[h] <= pb.vertical_budget and 1 <= s_budget[h] <= pb.slash_budget
+        v = select_one(vscore[h], int(v_budget[h]), pb.keep_first_cols)
+        s = select_one(sscore[h], int(s_budget[h]), pb.keep_local_band)
+        v_idx[h, :len(v)] = v; v_cnt[h] = len(v); s_idx[h, :len(s)] = s; s_cnt[h] = len(s)
+    return v_idx, v_cnt, s_idx, s_cnt
+
+
 def estimate(pb: Problem, q, k, heads=None):
     """Step 1.  q: [C][Hq][D] u16 (the chunk), k: [>=n_k][Hkv][D] u16.
     Returns vscore [nh][n_k], sscore [nh][n_k], lse_lastq [nh][W'] (fp64)."""

@@ -319,6 +319,38 @@ double vso_attention_recall(double lse_sparse, double lse_full) {
   return exp(lse_sparse - lse_full);
 }
 
+/* Attention recall of one head over a chunk: the mean over the chunk's rows of
+ * exp(lse_sparse - lse_full) ("Sparsity refinement" paragraph; the paper gives the
+ * per-query quantity and compares it with a threshold per head -- the mean over the rows
+ * is this build's reading of "the recall of a head").  A row with no selected key
+ * (lse_sparse = -inf) counts 0.  lse arrays are [rows]. */
+double vso_recall_mean(const double *lse_sparse, const double *lse_full, int64_t rows) {
+  double acc = 0.0;
+  for (int64_t i = 0; i < rows; ++i) {
+    const double r = exp(lse_sparse[i] - lse_full[i]);
+    acc += isfinite(r) ? r : 0.0;
+  }
+  return rows > 0 ? acc / (double)rows : 0.0;
+}
+
+/* One pass of the sparsity refinement (Algorithm 1) over the heads of a layer: a head whose
+ * recall is below the threshold gets dv more vertical and ds more slash lines, up to the
+ * given maxima.  Returns the number of heads whose configuration changed. */
+int vso_refine_step(int n_heads, const double *recall, double threshold, int32_t dv, int32_t ds,
+                    int32_t v_max, int32_t s_max, int32_t *v_budget, int32_t *s_budget) {
+  int changed = 0;
+  for (int h = 0; h < n_heads; ++h) {
+    if (!(recall[h] < threshold)) continue;
+    int32_t nv = v_budget[h] + dv, ns = s_budget[h] + ds;
+    if (nv > v_max) nv = v_max;
+    if (ns > s_max) ns = s_max;
+    if (nv != v_budget[h] || ns != s_budget[h]) ++changed;
+    v_budget[h] = nv;
+    s_budget[h] = ns;
+  }
+  return changed;
+}
+
 /* Number of OpenMP threads the calls above will use (reported beside timings). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -71,6 +71,12 @@ def lib() -> C.CDLL:
         L.vs_dense_causal_prefill.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_prefill_chunk.restype = C.c_int
         L.vs_prefill_chunk.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_select_heads.restype = C.c_int
+        L.vs_select_heads.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_attention_recall.restype = C.c_int
+        L.vs_attention_recall.argtypes = [P, vp, vp, vp, vp]
+        L.vs_refine_step.restype = C.c_int
+        L.vs_refine_step.argtypes = [P, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
         L.vs_set_option.restype = C.c_int
         L.vs_set_option.argtypes = [C.c_int, C.c_int64]
         L.vs_count_tiles.restype = C.c_int
@@ -81,7 +87,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
-           "vs_set_option"]
+           "vs_set_option", "vs_select_heads", "vs_attention_recall", "vs_refine_step"]
 
 
 def status_string(status: int) -> str:
@@ -199,6 +205,46 @@ def select(ck: Chunk, vscore, sscore, sets=None):
     _check(lib().vs_select(C.byref(p), _ptr(vscore), _ptr(sscore), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx),
                            _ptr(s_cnt), _ptr(ws) if n else C.c_void_p(0), n, _stream()), "vs_select")
     return v_idx, v_cnt, s_idx, s_cnt
+
+
+def select_heads(ck: Chunk, vscore, sscore, v_budget_h, s_budget_h, sets=None):
+    """vs_select_heads: vs_select with one (vertical, slash) budget pair per head (device int32 [Hq])."""
+    assert vscore.dtype == torch.float32 and vscore.is_contiguous() and vscore.shape == (ck.n_q_heads, ck.n_k)
+    assert sscore.dtype == torch.float32 and sscore.is_contiguous() and sscore.shape == (ck.n_q_heads, ck.n_k)
+    for t in (v_budget_h, s_budget_h):
+        assert t.dtype == torch.int32 and t.is_contiguous() and t.shape == (ck.n_q_heads,)
+    dev = vscore.device
+    v_idx, v_cnt, s_idx, s_cnt = alloc_index_sets(ck, dev) if sets is None else sets
+    _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt)
+    ws, n = _ws(ck, VS_WS_SELECT, dev)
+    p = ck.params()
+    _check(lib().vs_select_heads(C.byref(p), _ptr(vscore), _ptr(sscore), _ptr(v_budget_h), _ptr(s_budget_h),
+                                 _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx), _ptr(s_cnt),
+                                 _ptr(ws) if n else C.c_void_p(0), n, _stream()), "vs_select_heads")
+    return v_idx, v_cnt, s_idx, s_cnt
+
+
+def attention_recall(ck: Chunk, lse_sparse, lse_full):
+    """vs_attention_recall.  lse tensors fp32 [Hq][C] -> recall fp32 [Hq]."""
+    for t in (lse_sparse, lse_full):
+        assert t.dtype == torch.float32 and t.is_contiguous() and t.shape == (ck.n_q_heads, ck.q_len)
+    recall = torch.empty((ck.n_q_heads,), dtype=torch.float32, device=lse_sparse.device)
+    p = ck.params()
+    _check(lib().vs_attention_recall(C.byref(p), _ptr(lse_sparse), _ptr(lse_full), _ptr(recall), _stream()),
+           "vs_attention_recall")
+    return recall
+
+
+def refine_step(ck: Chunk, recall, threshold, add_vertical, add_slash, v_budget_h, s_budget_h):
+    """vs_refine_step: budgets (device int32 [Hq]) grow in place; returns a device int32[1] with
+    the number of heads that changed."""
+    assert recall.dtype == torch.float32 and recall.shape == (ck.n_q_heads,)
+    changed = torch.zeros((1,), dtype=torch.int32, device=recall.device)
+    p = ck.params()
+    _check(lib().vs_refine_step(C.byref(p), _ptr(recall), C.c_float(threshold), C.c_int32(add_vertical),
+                                C.c_int32(add_slash), _ptr(v_budget_h), _ptr(s_budget_h), _ptr(changed), _stream()),
+           "vs_refine_step")
+    return changed
 
 
 def _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt):

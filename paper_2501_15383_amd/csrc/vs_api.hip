@@ -136,7 +136,41 @@ int vs_select(const vs_params* p, const float* vscore, const float* sscore, int3
   if (!vscore || !sscore || !v_idx || !v_cnt || !s_idx || !s_cnt) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, select_ws_bytes(*p));
   if (rc != VS_OK) return rc;
-  return hip_status(launch_select(*p, vscore, sscore, v_idx, v_cnt, s_idx, s_cnt, ws, (hipStream_t)stream));
+  return hip_status(launch_select(*p, vscore, sscore, nullptr, nullptr, v_idx, v_cnt, s_idx, s_cnt, ws,
+                                  (hipStream_t)stream));
+}
+
+int vs_select_heads(const vs_params* p, const float* vscore, const float* sscore,
+                    const int32_t* v_budget_h, const int32_t* s_budget_h, int32_t* v_idx,
+                    int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void* ws, size_t ws_bytes,
+                    void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!vscore || !sscore || !v_budget_h || !s_budget_h || !v_idx || !v_cnt || !s_idx || !s_cnt)
+    return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, select_ws_bytes(*p));
+  if (rc != VS_OK) return rc;
+  return hip_status(launch_select(*p, vscore, sscore, v_budget_h, s_budget_h, v_idx, v_cnt, s_idx, s_cnt, ws,
+                                  (hipStream_t)stream));
+}
+
+int vs_attention_recall(const vs_params* p, const float* lse_sparse, const float* lse_full,
+                        float* recall, void* stream) {
+  int rc = check_params(p, false);
+  if (rc != VS_OK) return rc;
+  if (!lse_sparse || !lse_full || !recall) return VS_ERR_INVALID_ARG;
+  return hip_status(launch_recall(*p, lse_sparse, lse_full, recall, (hipStream_t)stream));
+}
+
+int vs_refine_step(const vs_params* p, const float* recall, float threshold, int32_t add_vertical,
+                   int32_t add_slash, int32_t* v_budget_h, int32_t* s_budget_h, int32_t* changed,
+                   void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!recall || !v_budget_h || !s_budget_h) return VS_ERR_INVALID_ARG;
+  if (!(threshold >= 0.f) || add_vertical < 0 || add_slash < 0) return VS_ERR_INVALID_ARG;
+  return hip_status(launch_refine(*p, recall, threshold, add_vertical, add_slash, v_budget_h, s_budget_h, changed,
+                                  (hipStream_t)stream));
 }
 
 int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, const void* v,

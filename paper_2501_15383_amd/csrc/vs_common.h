@@ -76,7 +76,12 @@ hipError_t launch_estimate(const vs_params& p, const void* q, const void* k, flo
 
 size_t select_ws_bytes(const vs_params& p);
 hipError_t launch_select(const vs_params& p, const float* vscore, const float* sscore,
+                         const int32_t* v_budget_h, const int32_t* s_budget_h,
                          int32_t* v_idx, int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt,
                          void* ws, hipStream_t st);
+hipError_t launch_recall(const vs_params& p, const float* lse_sparse, const float* lse_full, float* recall,
+                         hipStream_t st);
+hipError_t launch_refine(const vs_params& p, const float* recall, float threshold, int32_t dv, int32_t ds,
+                         int32_t* v_budget, int32_t* s_budget, int32_t* changed, hipStream_t st);
 
 }  // namespace vs

@@ -25,7 +25,9 @@ struct SelArgs {
   const float* vscore;
   const float* sscore;
   int64_t n;  // n_k
-  int32_t v_budget, s_budget, keep_v, keep_s;
+  int32_t v_budget, s_budget, keep_v, keep_s;  // budgets: row lengths of the outputs (maxima)
+  const int32_t* v_budget_h;  // optional per-head budgets (clamped to 1 .. maximum), else null
+  const int32_t* s_budget_h;
   int32_t* v_idx;
   int32_t* v_cnt;
   int32_t* s_idx;
@@ -36,9 +38,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
   const int h = blockIdx.x, kind = blockIdx.y;
   const int64_t n = a.n;
   const float* sc = (kind ? a.sscore : a.vscore) + (int64_t)h * n;
-  const int budget = kind ? a.s_budget : a.v_budget;
+  const int row_len = kind ? a.s_budget : a.v_budget;
+  const int32_t* per_head = kind ? a.s_budget_h : a.v_budget_h;
+  int budget = row_len;
+  if (per_head) {
+    budget = per_head[h];
+    budget = budget < 1 ? 1 : (budget > row_len ? row_len : budget);
+  }
   const int keep = kind ? a.keep_s : a.keep_v;
-  int32_t* out = (kind ? a.s_idx : a.v_idx) + (int64_t)h * budget;
+  int32_t* out = (kind ? a.s_idx : a.v_idx) + (int64_t)h * row_len;
   const int k = budget < n ? budget : (int)n;
   const int f = keep < k ? keep : k;  // forced entries 0..f-1
   const int kp = k - f;               // still to choose among indices f..n-1
@@ -48,7 +56,7 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
   __shared__ uint32_t sh_prefix, sh_krem;
   __shared__ uint32_t wtot[2][kSelWaves][2];
 
-  for (int t = tid; t < budget; t += kSelThreads) {
+  for (int t = tid; t < row_len; t += kSelThreads) {
     if (t < f) out[t] = t;
     else if (t >= k) out[t] = -1;
   }
@@ -130,14 +138,73 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
 size_t select_ws_bytes(const vs_params&) { return 0; }
 
 hipError_t launch_select(const vs_params& p, const float* vscore, const float* sscore,
+                         const int32_t* v_budget_h, const int32_t* s_budget_h,
                          int32_t* v_idx, int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void*,
                          hipStream_t st) {
   SelArgs a;
   a.vscore = vscore; a.sscore = sscore; a.n = p.q_start + p.q_len;
   a.v_budget = p.vertical_budget; a.s_budget = p.slash_budget;
   a.keep_v = p.keep_first_cols; a.keep_s = p.keep_local_band;
+  a.v_budget_h = v_budget_h; a.s_budget_h = s_budget_h;
   a.v_idx = v_idx; a.v_cnt = v_cnt; a.s_idx = s_idx; a.s_cnt = s_cnt;
   hipLaunchKernelGGL(k_select, dim3(p.n_q_heads, 2), dim3(kSelThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+// ---- sparsity refinement ("Sparsity refinement" paragraph and Algorithm 1) --------------------
+// recall[h] = mean over the chunk's rows of exp(lse_sparse - lse_full); a row without any
+// selected key counts 0.  One workgroup per head, fixed reduction tree.
+__global__ __launch_bounds__(256) void k_recall(const float* lse_sparse, const float* lse_full, int64_t rows,
+                                                float* recall) {
+  const int h = blockIdx.x, tid = threadIdx.x;
+  const float* ls = lse_sparse + (int64_t)h * rows;
+  const float* lf = lse_full + (int64_t)h * rows;
+  float acc = 0.f;
+  for (int64_t i = tid; i < rows; i += 256) {
+    const float r = __expf(ls[i] - lf[i]);
+    acc += (r == r && r <= 3.0e38f) ? r : 0.f;
+  }
+  __shared__ float part[256];
+  part[tid] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) part[tid] += part[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) recall[h] = rows > 0 ? part[0] / (float)rows : 0.f;
+}
+
+// One pass of Algorithm 1 over the heads: a head below the threshold gets dv / ds more lines.
+__global__ __launch_bounds__(256) void k_refine(const float* recall, float threshold, int32_t dv, int32_t ds,
+                                                int32_t v_max, int32_t s_max, int n_heads,
+                                                int32_t* v_budget, int32_t* s_budget, int32_t* changed) {
+  __shared__ int cnt;
+  if (threadIdx.x == 0) cnt = 0;
+  __syncthreads();
+  for (int h = threadIdx.x; h < n_heads; h += 256) {
+    if (recall[h] < threshold) {
+      int nv = v_budget[h] + dv, ns = s_budget[h] + ds;
+      nv = nv > v_max ? v_max : nv;
+      ns = ns > s_max ? s_max : ns;
+      if (nv != v_budget[h] || ns != s_budget[h]) atomicAdd(&cnt, 1);
+      v_budget[h] = nv;
+      s_budget[h] = ns;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && changed) *changed = cnt;
+}
+
+hipError_t launch_recall(const vs_params& p, const float* lse_sparse, const float* lse_full, float* recall,
+                         hipStream_t st) {
+  hipLaunchKernelGGL(k_recall, dim3(p.n_q_heads), dim3(256), 0, st, lse_sparse, lse_full, (int64_t)p.q_len, recall);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine(const vs_params& p, const float* recall, float threshold, int32_t dv, int32_t ds,
+                         int32_t* v_budget, int32_t* s_budget, int32_t* changed, hipStream_t st) {
+  hipLaunchKernelGGL(k_refine, dim3(1), dim3(256), 0, st, recall, threshold, dv, ds, p.vertical_budget,
+                     p.slash_budget, p.n_q_heads, v_budget, s_budget, changed);
   return hipGetLastError();
 }
 
