@@ -227,17 +227,27 @@ __global__ __launch_bounds__(64 * NW) void k_estimate(const EstArgs a) {
 }
 
 // lse2[h][r] = M + log2(L) over all range partials; rows >= W' get +inf (their P is 0).
-__global__ __launch_bounds__(64) void k_estimate_combine(const EstArgs a) {
-  const int h = blockIdx.x, r = threadIdx.x;
-  float M = -INFINITY, L = 0.f;
-  for (int rg = 0; rg < a.n_ranges; ++rg) {
-    const float* pp = a.part + (((int64_t)h * a.n_ranges + rg) * 64 + r) * 2;
-    const float m = pp[0], l = pp[1];
+// 16 groups of 64 threads each fold every 16th range, then group 0 folds the 16 results: a
+// fixed order, so the result is run-to-run identical.
+__global__ __launch_bounds__(1024) void k_estimate_combine(const EstArgs a) {
+  const int h = blockIdx.x, r = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  auto fold = [](float& M, float& L, float m, float l) {
     const float Mn = fmaxf(M, m);
     const float Mu = (Mn == -INFINITY) ? 0.f : Mn;
     L = L * __builtin_amdgcn_exp2f(M - Mu) + l * __builtin_amdgcn_exp2f(m - Mu);
     M = Mn;
+  };
+  float M = -INFINITY, L = 0.f;
+  for (int rg = grp; rg < a.n_ranges; rg += 16) {
+    const float* pp = a.part + (((int64_t)h * a.n_ranges + rg) * 64 + r) * 2;
+    fold(M, L, pp[0], pp[1]);
   }
+  __shared__ float sm[16][64], sl[16][64];
+  sm[grp][r] = M;
+  sl[grp][r] = L;
+  __syncthreads();
+  if (grp != 0) return;
+  for (int g2 = 1; g2 < 16; ++g2) fold(M, L, sm[g2][r], sl[g2][r]);
   const float l2 = M + __builtin_amdgcn_logf(L);
   a.lse2[(int64_t)h * 64 + r] = r < a.wp ? l2 : INFINITY;
   if (a.lse_lastq && r < a.wp) a.lse_lastq[(int64_t)h * a.wp + r] = l2 * kLn2;
@@ -265,7 +275,7 @@ template <int D, int NW>
 static hipError_t launch_est(const EstArgs& a, int hb, hipStream_t st) {
   const dim3 grid(a.n_ranges, a.n_kv_heads, hb);
   hipLaunchKernelGGL((k_estimate<D, NW, 0>), grid, dim3(64 * NW), 0, st, a);
-  hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(1024), 0, st, a);
   hipLaunchKernelGGL((k_estimate<D, NW, 1>), grid, dim3(64 * NW), 0, st, a);
   return hipGetLastError();
 }

@@ -52,6 +52,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
   const int kp = k - f;               // still to choose among indices f..n-1
 
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  // 16 copies of the 256-bin histogram, copy = lane % 16 in consecutive banks: the top digits of
+  // real scores crowd into a few bins, and 64 lanes adding to one address would serialise
+  __shared__ uint32_t hist16[256 * 16];
   __shared__ uint32_t hist[256];
   __shared__ uint32_t sh_prefix, sh_krem;
   __shared__ uint32_t wtot[2][kSelWaves][2];
@@ -68,11 +71,29 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
   for (int pass = 0; pass < 4; ++pass) {
     const int shift = 24 - 8 * pass;
     const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    if (tid < 256) hist[tid] = 0;
+    for (int x = tid; x < 256 * 16; x += kSelThreads) hist16[x] = 0;
     __syncthreads();
-    for (int64_t i = f + tid; i < n; i += kSelThreads) {
-      const uint32_t key = order_key(sc[i]);
-      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    // kSelItems independent loads per thread in flight (the pass is latency-bound otherwise)
+    for (int64_t base = f; base < n; base += (int64_t)kSelThreads * kSelItems) {
+      uint32_t key[kSelItems];
+      bool ok[kSelItems];
+#pragma unroll
+      for (int e = 0; e < kSelItems; ++e) {
+        const int64_t i = base + (int64_t)e * kSelThreads + tid;
+        ok[e] = i < n;
+        key[e] = ok[e] ? order_key(sc[i]) : 0u;
+      }
+#pragma unroll
+      for (int e = 0; e < kSelItems; ++e)
+        if (ok[e] && (key[e] & himask) == prefix)
+          atomicAdd(&hist16[(((key[e] >> shift) & 255u) << 4) | (lane & 15)], 1u);
+    }
+    __syncthreads();
+    if (tid < 256) {
+      uint32_t c = 0;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) c += hist16[(tid << 4) | x];
+      hist[tid] = c;
     }
     __syncthreads();
     if (tid == 0) {
