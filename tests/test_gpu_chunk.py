@@ -41,3 +41,36 @@ def test_small_configuration_all_chunks(bv, bs):
         _, lse_d = vs.dense_causal_prefill(ck, qd, Kd, Vd, want_lse=True)
         rec = torch.exp(lse - lse_d)
         assert (rec > 0).all() and (rec <= 1 + 1e-4).all()
+
+
+def test_clustered_slash_workload_last_chunks():
+    """The extra workload with planted, clustered slash lines (scaled down): whole path against the
+    oracle, index sets by the band rule, attention on the GPU's own sets."""
+    from gpu_util import check_index_sets, f64
+    w = vsgen.scaled(vsgen.WORKLOADS["7b_1m_local"], n_ctx=12288, chunk=1024, n_q_heads=4, n_kv_heads=2,
+                     vertical_budget=96, slash_budget=320, n_sink=24)
+    K, V = vsgen.make_kv(w)
+    Kd, Vd = K.cuda(), V.cuda()
+    ku, vu = vsgen.as_u16(K), vsgen.as_u16(V)
+    for ci in (w.n_chunks - 2, w.n_chunks - 1):
+        s = ci * w.chunk
+        Q = vsgen.make_q(w, s, s + w.chunk)
+        pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, w.chunk, s, w.softmax_scale,
+                            vertical_budget=w.vertical_budget, slash_budget=w.slash_budget)
+        ck = chunk_of(pb)
+        qd = Q.cuda()
+        vsc, ssc, _ = vs.estimate(ck, qd, Kd)
+        sets = vs.select(ck, vsc, ssc)
+        out, lse = vs.sparse_attn_prefill(ck, qd, Kd, Vd, *sets, want_lse=True)
+        torch.cuda.synchronize()
+        rvs, rss, _ = oracle.estimate(pb, vsgen.as_u16(Q), ku)
+        np.testing.assert_allclose(f64(vsc), rvs, rtol=2e-4, atol=1e-7)
+        np.testing.assert_allclose(f64(ssc), rss, rtol=2e-4, atol=1e-7)
+        v_idx, v_cnt, s_idx, s_cnt = [x.cpu().numpy() for x in sets]
+        for h in range(w.n_q_heads):
+            check_index_sets(rvs[h], v_idx[h], v_cnt[h], w.vertical_budget, 1, f"chunk {ci} head {h} vertical")
+            check_index_sets(rss[h], s_idx[h], s_cnt[h], w.slash_budget, 64, f"chunk {ci} head {h} slash")
+        # the planted structure shows: most selected offsets are small
+        assert np.median(s_idx[0][: s_cnt[0]]) < pb.n_k / 8
+        ref_out, ref_lse = oracle.sparse_attention(pb, vsgen.as_u16(Q), ku, vu, v_idx, v_cnt, s_idx, s_cnt)
+        assert_attn_close(out, lse, ref_out, ref_lse, f"clustered chunk {ci}")

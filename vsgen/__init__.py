@@ -19,6 +19,10 @@ Qwen2.5-1M models, section 2 table: 7B = 28 query / 4 KV heads, 14B = 40 / 8):
      and every query gets + u, with u a seeded unit vector (per KV head).
      This plants vertical lines; no slash structure is planted.
   5. one rounding to bf16 (round to nearest even).
+Extra, not one of the five configurations ("7b_1m_local"): before RoPE a shared seeded
+vector (per KV head, length local_mag) is added to every query and key, so that q_i . k_j
+gains a term that depends only on i - j and decays slowly with it -- slash lines that
+cluster at small offsets, as the attention maps of trained models show them.
 """
 from __future__ import annotations
 
@@ -52,6 +56,7 @@ class Workload:
     sink_mag: float = 3.0      # a_g = sink_mag * 2**(g % 4) when sink_mag_per_head
     sink_mag_per_head: bool = False
     heavy_tail: bool = False
+    local_mag: float = 0.0     # > 0: planted slash structure (see the module docstring)
     rope_theta: float = 1.0e7
     config_id: int = 0
     seed: int = BASE_SEED
@@ -79,6 +84,9 @@ WORKLOADS = {
     "14b_1m": Workload("14b_1m", 40, 8, 128, 1048576, 32768, vertical_budget=2000,
                        slash_budget=8192, n_sink=512, n_sink_min=32, sink_mag_per_head=True,
                        heavy_tail=True, config_id=4),
+    # extra: the 7B configuration with planted, clustered slash lines (not a BASELINE configuration)
+    "7b_1m_local": Workload("7b_1m_local", 28, 4, 128, 1048576, 32768, vertical_budget=1000,
+                            slash_budget=6096, n_sink=256, sink_mag_per_head=True, local_mag=8.0, config_id=5),
 }
 
 
@@ -153,6 +161,13 @@ def unit_vectors(w: Workload, device="cpu") -> torch.Tensor:
     return u / u.norm(dim=-1, keepdim=True)
 
 
+def local_vectors(w: Workload, device="cpu") -> torch.Tensor:
+    """One seeded unit vector per KV head for the planted slash structure, fp32 [Hkv][D]."""
+    idx = torch.arange(w.n_kv_heads * w.head_dim, dtype=torch.int64, device=device)
+    u = _normal(idx, _key(w.seed, w.config_id, _T_U, 1)).view(w.n_kv_heads, w.head_dim)
+    return u / u.norm(dim=-1, keepdim=True)
+
+
 def sink_counts(w: Workload) -> list[int]:
     if w.n_sink_min < 0:
         return [w.n_sink] * w.n_kv_heads
@@ -194,9 +209,11 @@ def _to_bf16(x: torch.Tensor) -> torch.Tensor:
 def make_q(w: Workload, t0: int, t1: int, device="cpu") -> torch.Tensor:
     """Queries of tokens t0..t1-1: bf16 [t1-t0][Hq][D]."""
     x = _normal(_counters(t0, t1, w.n_q_heads, w.head_dim, device), _key(w.seed, w.config_id, _T_Q, 0))
+    g_of_h = torch.arange(w.n_q_heads, device=device) // (w.n_q_heads // w.n_kv_heads)
+    if w.local_mag > 0:
+        x = x + w.local_mag * local_vectors(w, device)[g_of_h].unsqueeze(0)
     x = _rope(x, t0, w.rope_theta)
     if w.n_sink > 0:
-        g_of_h = torch.arange(w.n_q_heads, device=device) // (w.n_q_heads // w.n_kv_heads)
         x = x + unit_vectors(w, device)[g_of_h].unsqueeze(0)
     return _to_bf16(x)
 
@@ -210,6 +227,8 @@ def _make_kv_slab(w: Workload, t0: int, t1: int, device, sinks, mags, u):
         pick = _uniform(th, _key(w.seed, w.config_id, _T_TAILP, 0)) <= 0.05
         z = _normal(th, _key(w.seed, w.config_id, _T_TAILZ, 0))
         k = k * torch.where(pick, torch.exp(z), torch.ones_like(z))
+    if w.local_mag > 0:
+        k = k + w.local_mag * local_vectors(w, device).unsqueeze(0)
     k = _rope(k, t0, w.rope_theta)
     for g in range(w.n_kv_heads):
         pos = sinks[g]
