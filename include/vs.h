@@ -177,6 +177,26 @@ int vs_refine_step(const vs_params *p, const float *recall, float threshold,
                    int32_t add_vertical, int32_t add_slash, int32_t *v_budget_h,
                    int32_t *s_budget_h, int32_t *changed, void *stream);
 
+/* Cost model and chunk planner (host functions; sec. 6.3 "Dynamic Chunked Pipeline
+ * Parallelism": chunk sizes are adjusted to the complexity of the attention
+ * kernel so that every chunk takes about the same time).  The unit is one 64x64
+ * tile of one head.
+ *   VS_COST_DENSE    query block m (absolute index) costs m + 1 tiles
+ *   VS_COST_SPARSE   expected tiles when the slash_budget offsets scatter
+ *                    uniformly over the n_k = q_start + q_len keys of the chunk:
+ *                    (m + 1) (1 - (1 - 2/nb)^Bs) with nb = ceil(n_k / 64), plus
+ *                    ceil(min(Bv, n_k) / 64) tiles of gathered columns
+ * vs_chunk_cost returns the sum over the query blocks of the chunk (< 0 on bad
+ * arguments).  vs_plan_chunks writes n_chunks + 1 ascending token boundaries,
+ * bounds[0] = 0, bounds[n_chunks] = n_ctx, the inner ones multiples of 64 chosen
+ * so that the chunk costs are as equal as 64-token steps allow; returns VS_OK or
+ * VS_ERR_INVALID_ARG (n_chunks < 1, n_ctx < 64 n_chunks, null pointer). */
+enum { VS_COST_DENSE = 0, VS_COST_SPARSE = 1 };
+double vs_chunk_cost(int64_t q_start, int64_t q_len, int32_t model,
+                     int32_t vertical_budget, int32_t slash_budget);
+int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model,
+                   int32_t vertical_budget, int32_t slash_budget, int64_t *bounds);
+
 /* Host: process-wide tuning switches (no device call; not thread-safe against
  * concurrent launches).  Returns VS_OK or VS_ERR_INVALID_ARG.
  *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per sync segment of the

@@ -77,6 +77,10 @@ def lib() -> C.CDLL:
         L.vs_attention_recall.argtypes = [P, vp, vp, vp, vp]
         L.vs_refine_step.restype = C.c_int
         L.vs_refine_step.argtypes = [P, vp, C.c_float, C.c_int32, C.c_int32, vp, vp, vp, vp]
+        L.vs_chunk_cost.restype = C.c_double
+        L.vs_chunk_cost.argtypes = [C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32]
+        L.vs_plan_chunks.restype = C.c_int
+        L.vs_plan_chunks.argtypes = [C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         L.vs_set_option.restype = C.c_int
         L.vs_set_option.argtypes = [C.c_int, C.c_int64]
         L.vs_count_tiles.restype = C.c_int
@@ -87,7 +91,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
-           "vs_set_option", "vs_select_heads", "vs_attention_recall", "vs_refine_step"]
+           "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step"]
 
 
 def status_string(status: int) -> str:
@@ -141,6 +145,22 @@ def _stream():
 def _check(rc, where):
     if rc != VS_OK:
         raise VsError(rc, where)
+
+
+VS_COST_DENSE, VS_COST_SPARSE = 0, 1
+
+
+def chunk_cost(q_start: int, q_len: int, model: int, vertical_budget: int = 1, slash_budget: int = 1) -> float:
+    """vs_chunk_cost (host): modelled 64x64 tiles per head of one chunk."""
+    return float(lib().vs_chunk_cost(int(q_start), int(q_len), int(model), int(vertical_budget), int(slash_budget)))
+
+
+def plan_chunks(n_ctx: int, n_chunks: int, model: int, vertical_budget: int = 1, slash_budget: int = 1):
+    """vs_plan_chunks (host): n_chunks + 1 token boundaries of chunks of about equal modelled cost."""
+    bounds = (C.c_int64 * (n_chunks + 1))()
+    _check(lib().vs_plan_chunks(int(n_ctx), int(n_chunks), int(model), int(vertical_budget), int(slash_budget), bounds),
+           "vs_plan_chunks")
+    return list(bounds)
 
 
 def set_option(which: int, value: int) -> None:

@@ -101,6 +101,56 @@ const char* vs_status_string(int status) {
   }
 }
 
+double vs_chunk_cost(int64_t q_start, int64_t q_len, int32_t model, int32_t vertical_budget,
+                     int32_t slash_budget) {
+  if (q_start < 0 || q_len < 1 || q_start % kBlock != 0) return -1.0;
+  if (model != VS_COST_DENSE && model != VS_COST_SPARSE) return -1.0;
+  if (model == VS_COST_SPARSE && (vertical_budget < 1 || slash_budget < 1)) return -1.0;
+  const int64_t m0 = q_start / kBlock, nqb = ceil_div(q_len, kBlock);
+  // sum over m = m0 .. m0 + nqb - 1 of (m + 1)
+  const double causal = (double)nqb * (double)m0 + 0.5 * (double)nqb * (double)(nqb + 1);
+  if (model == VS_COST_DENSE) return causal;
+  const int64_t n_k = q_start + q_len, nb = ceil_div(n_k, kBlock);
+  const double bs = (double)(slash_budget < n_k ? slash_budget : n_k);
+  const double density = nb <= 2 ? 1.0 : 1.0 - pow(1.0 - 2.0 / (double)nb, bs);
+  const double bv = (double)(vertical_budget < n_k ? vertical_budget : n_k);
+  return causal * density + (double)nqb * ceil(bv / kBlock);
+}
+
+int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model, int32_t vertical_budget,
+                   int32_t slash_budget, int64_t* bounds) {
+  if (!bounds || n_chunks < 1 || n_ctx < (int64_t)kBlock * n_chunks) return VS_ERR_INVALID_ARG;
+  if (vs_chunk_cost(0, kBlock, model, vertical_budget, slash_budget) < 0) return VS_ERR_INVALID_ARG;
+  const int64_t nb = ceil_div(n_ctx, kBlock);  // boundaries move in whole blocks
+  auto cost = [&](int64_t b0, int64_t b1) {     // blocks [b0, b1)
+    const int64_t t0 = b0 * kBlock, t1 = b1 * kBlock < n_ctx ? b1 * kBlock : n_ctx;
+    return vs_chunk_cost(t0, t1 - t0, model, vertical_budget, slash_budget);
+  };
+  // start from equal sizes, then a few rounds of: target = mean cost; cut greedily at it
+  for (int c = 0; c <= n_chunks; ++c) bounds[c] = nb * c / n_chunks;
+  for (int round = 0; round < 8; ++round) {
+    double total = 0;
+    for (int c = 0; c < n_chunks; ++c) total += cost(bounds[c], bounds[c + 1]);
+    const double target = total / n_chunks;
+    int64_t b = 0;
+    for (int c = 1; c < n_chunks; ++c) {
+      // smallest end e in (b, nb - (n_chunks - c)] whose cost reaches the target (cost grows with e)
+      int64_t lo = b + 1, hi = nb - (n_chunks - c);
+      while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (cost(b, mid) >= target) hi = mid; else lo = mid + 1;
+      }
+      // the end just below may be closer to the target
+      if (lo > b + 1 && fabs(cost(b, lo - 1) - target) <= fabs(cost(b, lo) - target)) --lo;
+      bounds[c] = lo;
+      b = lo;
+    }
+  }
+  for (int c = 0; c < n_chunks; ++c) bounds[c] *= kBlock;
+  bounds[n_chunks] = n_ctx;
+  return VS_OK;
+}
+
 int vs_set_option(int which, int64_t value) {
   switch (which) {
     case VS_OPT_ATTN_SEGMENT_BLOCKS:
