@@ -81,6 +81,8 @@ def main():
     ap.add_argument("--n-ctx", type=int, default=0, help="override the context length (tokens)")
     ap.add_argument("--segment-blocks", type=int, default=0,
                     help="64-key blocks per key segment of the sparse launch (0 = the library's choice)")
+    ap.add_argument("--layer-plan", choices=["equal", "dense", "sparse"], default="equal",
+                    help="chunk boundaries of --layer: equal lengths, or vs_plan_chunks with that cost model")
     ap.add_argument("--layer", action="store_true",
                     help="also time every chunk of the context once (whole-layer prefill); needs the last chunk")
     ap.add_argument("--no-dense", action="store_true")
@@ -201,37 +203,49 @@ def main():
     layer = None
     if args.layer and not w.dense and ci == w.n_chunks - 1:
         per_chunk = []
+        if args.layer_plan == "equal":
+            bounds = [min(i * w.chunk, w.n_ctx) for i in range(w.n_chunks + 1)]
+        else:
+            bounds = vs.plan_chunks(w.n_ctx, w.n_chunks, vs.VS_COST_DENSE if args.layer_plan == "dense" else vs.VS_COST_SPARSE,
+                                    bv, bs)
+        out_l = torch.empty((max(b - a for a, b in zip(bounds, bounds[1:])), w.n_q_heads, w.head_dim),
+                            dtype=torch.bfloat16, device=dev) if args.layer_plan != "equal" else out
+        ws_e_l, ws_a_l = ws_e, ws_a
+        if args.layer_plan != "equal":   # chunks longer than the equal ones need larger workspaces
+            cks = [vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, b - a, a, w.softmax_scale, last_q=w.last_q,
+                            vertical_budget=bv, slash_budget=bs) for a, b in zip(bounds, bounds[1:])]
+            ws_e_l = torch.empty(max(vs.workspace_bytes(c, vs.VS_WS_ESTIMATE) for c in cks), dtype=torch.uint8, device=dev)
+            ws_a_l = torch.empty(max(vs.workspace_bytes(c, vs.VS_WS_SPARSE) for c in cks), dtype=torch.uint8, device=dev)
         for i in range(w.n_chunks):
-            si = i * w.chunk
-            Ci = min(w.chunk, w.n_ctx - si)
+            si, Ci = bounds[i], bounds[i + 1] - bounds[i]
             cki = vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, Ci, si, w.softmax_scale, last_q=w.last_q,
                            vertical_budget=bv, slash_budget=bs, keep_first_cols=w.keep_first_cols,
                            keep_local_band=w.keep_local_band)
             Qi = vsgen.make_q(w, si, si + Ci, device=dev)
             nki = si + Ci
             vsc_i, ssc_i = vscore[:, :nki].contiguous(), sscore[:, :nki].contiguous()
-            oi = out[:Ci]
+            oi = out_l[:Ci]
             e = _events(4)
             torch.cuda.synchronize()
             e[0].record()
-            vs.estimate(cki, Qi, K, vscore=vsc_i, sscore=ssc_i, ws=ws_e)
+            vs.estimate(cki, Qi, K, vscore=vsc_i, sscore=ssc_i, ws=ws_e_l)
             vs.select(cki, vsc_i, ssc_i, sets=sets)
             e[1].record()
-            vs.sparse_attn_prefill(cki, Qi, K, V, *sets, out=oi, ws=ws_a)
+            vs.sparse_attn_prefill(cki, Qi, K, V, *sets, out=oi, ws=ws_a_l)
             e[2].record()
             if not args.no_dense:
-                vs.dense_causal_prefill(cki, Qi, K, V, out=oi, ws=ws_a)
+                vs.dense_causal_prefill(cki, Qi, K, V, out=oi, ws=ws_a_l)
             e[3].record()
             torch.cuda.synchronize()
             tl = vs.count_tiles(cki, *sets).sum().item()
             dt = w.n_q_heads * sum(si // 64 + qb + 1 for qb in range((Ci + 63) // 64))
-            per_chunk.append({"chunk": i, "sparse_ms": e[0].elapsed_time(e[2]), "estimate_select_ms": e[0].elapsed_time(e[1]),
+            per_chunk.append({"chunk": i, "q_start": si, "q_len": Ci, "sparse_ms": e[0].elapsed_time(e[2]), "estimate_select_ms": e[0].elapsed_time(e[1]),
                               "dense_ms": None if args.no_dense else e[2].elapsed_time(e[3]),
                               "computed_fraction": tl / dt})
             del Qi, vsc_i, ssc_i
         tot_s = sum(c["sparse_ms"] for c in per_chunk)
         tot_d = None if args.no_dense else sum(c["dense_ms"] for c in per_chunk)
-        layer = {"chunks": w.n_chunks, "sparse_ms_total": tot_s, "dense_ms_total": tot_d,
+        layer = {"chunks": w.n_chunks, "plan": args.layer_plan, "sparse_ms_total": tot_s, "dense_ms_total": tot_d,
                  "speedup": (tot_d / tot_s) if tot_d else None, "per_chunk": per_chunk}
 
     traffic = None

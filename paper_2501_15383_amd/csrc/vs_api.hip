@@ -126,23 +126,28 @@ int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model, int32_t verti
     const int64_t t0 = b0 * kBlock, t1 = b1 * kBlock < n_ctx ? b1 * kBlock : n_ctx;
     return vs_chunk_cost(t0, t1 - t0, model, vertical_budget, slash_budget);
   };
-  // start from equal sizes, then a few rounds of: target = mean cost; cut greedily at it
+  // start from equal sizes, then a few rounds of: target = mean cost; boundary c goes where the
+  // cost of chunks 0 .. c-1 together is closest to c targets (so rounding does not pile up in
+  // the last chunk).  Rounds are needed because the sparse cost of a chunk depends on its end.
   for (int c = 0; c <= n_chunks; ++c) bounds[c] = nb * c / n_chunks;
   for (int round = 0; round < 8; ++round) {
     double total = 0;
     for (int c = 0; c < n_chunks; ++c) total += cost(bounds[c], bounds[c + 1]);
     const double target = total / n_chunks;
     int64_t b = 0;
+    double before = 0;  // cost of the chunks already cut
     for (int c = 1; c < n_chunks; ++c) {
-      // smallest end e in (b, nb - (n_chunks - c)] whose cost reaches the target (cost grows with e)
+      const double want = target * c - before;
+      // smallest end e in (b, nb - (n_chunks - c)] whose cost reaches `want` (cost grows with e)
       int64_t lo = b + 1, hi = nb - (n_chunks - c);
       while (lo < hi) {
         const int64_t mid = lo + (hi - lo) / 2;
-        if (cost(b, mid) >= target) hi = mid; else lo = mid + 1;
+        if (cost(b, mid) >= want) hi = mid; else lo = mid + 1;
       }
-      // the end just below may be closer to the target
-      if (lo > b + 1 && fabs(cost(b, lo - 1) - target) <= fabs(cost(b, lo) - target)) --lo;
+      // the end just below may be closer
+      if (lo > b + 1 && fabs(cost(b, lo - 1) - want) <= fabs(cost(b, lo) - want)) --lo;
       bounds[c] = lo;
+      before += cost(b, lo);
       b = lo;
     }
   }

@@ -55,8 +55,11 @@ struct AttnArgs {
   float scale_log2;  // softmax_scale * log2(e)
   // persistent launch: n_wg workgroups, workgroup b is member b / 8 of group b % 8 (the groups
   // follow the round-robin of workgroups over the 8 XCDs); in round r group g works on
-  // group-round k = 8 r + g = (chunk of `members` consecutive query tiles, head), one tile each
-  int32_t n_wg, members, n_chunks;
+  // group-round k = 8 r + g, one query tile per member.  The top n_full * members tiles of
+  // every head go first, as (chunk of `members` consecutive tiles, head) rounds, latest chunks
+  // first; the n_rem tiles per head that are left are packed, head after head, into the rounds
+  // that follow, so that only the very last round can have idle members.
+  int32_t n_wg, members, n_full, n_rem;
   // pace keeping: arrive[g][s] counts the members of group g that are done with key blocks
   // [s * sync_blocks, (s + 1) * sync_blocks) over all rounds so far
   int32_t sync_blocks, n_sync;
@@ -139,14 +142,23 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // the XCD's L2, so that a K/V block is fetched from memory once per group and round.
   // Waiting is bounded and only shapes the timing: results never depend on it.
   const int grp = blockIdx.x & 7, member = blockIdx.x >> 3;
-  const int n_gr = a.n_chunks * a.n_q_heads;      // group-rounds: latest chunks first, heads inside
+  const int n_full_gr = a.n_full * a.n_q_heads;   // full rounds: latest chunks first, heads inside
+  const int n_gr = n_full_gr + (a.n_rem * a.n_q_heads + a.members - 1) / a.members;
   uint32_t* const arr = a.arrive + (int64_t)grp * a.n_sync;
   const int s_glob_top = (int)((n_k - 1) / 64) / a.sync_blocks;  // highest sync segment of the chunk
   for (int rnd = 0; rnd * 8 + grp < n_gr; ++rnd) {
   const int gr = rnd * 8 + grp;
-  const int chunk = a.n_chunks - 1 - gr / a.n_q_heads, h = gr % a.n_q_heads;
+  int h, qt;
+  if (gr < n_full_gr) {
+    h = gr % a.n_q_heads;
+    qt = a.n_rem + (a.n_full - 1 - gr / a.n_q_heads) * a.members + (a.members - 1 - member);
+  } else {  // packed rounds: unit u = (head, tile below n_rem), tiles descending inside a head
+    const int u = (gr - n_full_gr) * a.members + member;
+    h = u / a.n_rem;
+    qt = h < a.n_q_heads ? a.n_rem - 1 - u % a.n_rem : a.n_qtiles;
+    if (h >= a.n_q_heads) h = 0;
+  }
   const int g = h / a.group;
-  const int qt = chunk * a.members + (a.members - 1 - member);
   const uint32_t expected = (uint32_t)(rnd + 1) * (uint32_t)a.members;
   // marks key segments seg_done - 1, ..., s_new done for this member, then holds the workgroup
   // back (wave 0 polls, the others meet it at the step barrier) until the whole group is done
@@ -860,10 +872,12 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
   }
   int members = (2 * n_cu) / 8;
   if (members < 1) members = 1;
-  if (members > a.n_qtiles) members = a.n_qtiles;  // short chunks: fewer, not idle, workgroups
+  const int64_t units = (int64_t)a.n_qtiles * a.n_q_heads;
+  if (units < 8 * (int64_t)members) members = (int)ceil_div(units, 8);  // small launches: no idle workgroups
   a.members = members;
   a.n_wg = 8 * members;
-  a.n_chunks = (int)ceil_div(a.n_qtiles, members);
+  a.n_full = a.n_qtiles / members;
+  a.n_rem = a.n_qtiles - a.n_full * members;
   a.sync_blocks = attn_sync_blocks(p);
   a.n_sync = (int)ceil_div(ceil_div(p.q_start + p.q_len, kBlock), a.sync_blocks);
   a.arrive = (uint32_t*)sync_ws;

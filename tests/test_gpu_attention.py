@@ -138,3 +138,18 @@ def test_sparse_with_other_sync_segments_matches_oracle(seg_blocks, hq, hkv, d, 
     finally:
         vs.set_option(vs.VS_OPT_ATTN_SEGMENT_BLOCKS, 0)
     assert_attn_close(out, lse, ref_out, ref_lse, f"sync {seg_blocks}: sparse {hq}/{hkv}/{d} C={c} s={s}")
+
+
+def test_sparse_cost_model_follows_counted_tiles():
+    """vs_chunk_cost(VS_COST_SPARSE) against the tiles the block list really holds when the slash offsets
+    scatter uniformly (the model's premise).  One head's count scatters by about 2 % around the expectation,
+    so the mean over 16 heads is compared (within 2 %); gathered columns never exceed the model's."""
+    rng = np.random.default_rng(303)
+    hq, d, c, s, nv, ns = 16, 128, 2048, 63488, 500, 300
+    pb = oracle.Problem(hq, 1, d, c, s, 0.1, vertical_budget=nv, slash_budget=ns, keep_first_cols=0, keep_local_band=0)
+    sets = _rand_sets(rng, pb, nv, ns)
+    tiles = vs.count_tiles(chunk_of(pb), *[_t(x) for x in sets]).cpu().numpy()
+    slash_model = vs.chunk_cost(s, c, vs.VS_COST_SPARSE, 1, ns) - (c // 64)   # one tile of columns per query block
+    column_model = vs.chunk_cost(s, c, vs.VS_COST_SPARSE, nv, ns) - slash_model
+    assert abs(tiles[:, 0].mean() - slash_model) <= 0.02 * slash_model, (tiles[:, 0].mean(), slash_model)
+    assert (tiles[:, 1] <= column_model).all()
