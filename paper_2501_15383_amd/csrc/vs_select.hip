@@ -1,20 +1,33 @@
 // Selection of the vertical and slash lines (section 5.2, MInference paragraph: critical
 // tokens are chosen by the vertical-slash pattern with a per-head count of vertical and
-// diagonal lines).  One workgroup per (head, kind) problem: exact top-k of up to 2^31 fp32
-// scores without sorting.
-//   1. forced entries (the lowest `keep` indices) are taken first;
+// diagonal lines).  Exact top-k of up to 2^31 fp32 scores per (head, kind) row without sorting:
+//   1. forced entries (the lowest `keep` indices) are taken first (k_sel_init);
 //   2. a most-significant-digit radix select (4 x 8 bits on an order-preserving integer image
-//      of the float) finds the threshold key T and how many entries equal to T are needed;
-//   3. one ordered compaction pass emits indices in ascending order: every key > T, and the
-//      lowest-index keys == T (ties go to the lower index).  Ranks come from wave ballots and
-//      a 16-entry cross-wave scan, all integer, so the result is exact and deterministic.
+//      of the float) finds the threshold key T and how many entries equal to T are needed.
+//      A row is cut into slices, one workgroup each; every workgroup adds its 256-bin
+//      histogram to the row's, and the workgroup that finishes last picks the digit
+//      (k_sel_hist, once per digit);
+//   3. the keys > T and == T of every slice are counted (k_sel_count), and one ordered
+//      compaction pass emits indices in ascending order: every key > T, and the lowest-index
+//      keys == T (ties go to the lower index).  Ranks come from the slice counts, wave
+//      ballots and a 16-entry cross-wave scan (k_sel_write).
+// All of it is integer work, so the result is exact and run-to-run identical.
 #include "vs_common.h"
 
 namespace vs {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
-constexpr int kSelItems = 8;  // elements per lane per compaction step
+constexpr int kSelItems = 8;  // elements per lane per step
+constexpr int kSelStep = kSelThreads * kSelItems;
+constexpr int kSelMaxSlices = 64;
+// control block of a row in the workspace, in 32-bit words
+constexpr int kWHist = 0;      // [4][256] histogram of every digit
+constexpr int kWDone = 1024;   // [4] workgroups done with the digit
+constexpr int kWState = 1028;  // [5][2] (prefix, entries still to find) before digit 0..3 and after
+constexpr int kWForced = 1038, kWChoose = 1039;
+constexpr int kWCount = 1056;  // [slices][2] keys > T, keys == T
+constexpr int kSelRowWords = kWCount + 2 * kSelMaxSlices;
 
 __device__ __forceinline__ uint32_t order_key(float x) {
   const uint32_t b = __float_as_uint(x);
@@ -25,6 +38,8 @@ struct SelArgs {
   const float* vscore;
   const float* sscore;
   int64_t n;  // n_k
+  int64_t slice_len;
+  int32_t n_q_heads;
   int32_t v_budget, s_budget, keep_v, keep_s;  // budgets: row lengths of the outputs (maxima)
   const int32_t* v_budget_h;  // optional per-head budgets (clamped to 1 .. maximum), else null
   const int32_t* s_budget_h;
@@ -32,102 +47,190 @@ struct SelArgs {
   int32_t* v_cnt;
   int32_t* s_idx;
   int32_t* s_cnt;
+  uint32_t* ws;  // [2 Hq][kSelRowWords]
 };
 
-__global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
-  const int h = blockIdx.x, kind = blockIdx.y;
-  const int64_t n = a.n;
-  const float* sc = (kind ? a.sscore : a.vscore) + (int64_t)h * n;
-  const int row_len = kind ? a.s_budget : a.v_budget;
+// row = kind * Hq + h
+struct SelRow {
+  const float* sc;
+  int32_t* out;
+  uint32_t* w;
+  int row_len;
+};
+__device__ __forceinline__ SelRow sel_row(const SelArgs& a, int row) {
+  const int kind = row >= a.n_q_heads, h = row - kind * a.n_q_heads;
+  SelRow r;
+  r.sc = (kind ? a.sscore : a.vscore) + (int64_t)h * a.n;
+  r.row_len = kind ? a.s_budget : a.v_budget;
+  r.out = (kind ? a.s_idx : a.v_idx) + (int64_t)h * r.row_len;
+  r.w = a.ws + (int64_t)row * kSelRowWords;
+  return r;
+}
+
+// Forced entries, padding, the count, and a cleared control block.
+__global__ __launch_bounds__(256) void k_sel_init(const SelArgs a) {
+  const int row = blockIdx.x, kind = row >= a.n_q_heads, h = row - kind * a.n_q_heads;
+  const SelRow r = sel_row(a, row);
   const int32_t* per_head = kind ? a.s_budget_h : a.v_budget_h;
-  int budget = row_len;
+  int budget = r.row_len;
   if (per_head) {
     budget = per_head[h];
-    budget = budget < 1 ? 1 : (budget > row_len ? row_len : budget);
+    budget = budget < 1 ? 1 : (budget > r.row_len ? r.row_len : budget);
   }
   const int keep = kind ? a.keep_s : a.keep_v;
-  int32_t* out = (kind ? a.s_idx : a.v_idx) + (int64_t)h * row_len;
-  const int k = budget < n ? budget : (int)n;
+  const int k = budget < a.n ? budget : (int)a.n;
   const int f = keep < k ? keep : k;  // forced entries 0..f-1
   const int kp = k - f;               // still to choose among indices f..n-1
+  const int tid = threadIdx.x;
+  for (int x = tid; x < kSelRowWords; x += 256) {
+    uint32_t v = 0;
+    if (x == kWState + 1 || x == kWChoose) v = (uint32_t)kp;
+    if (x == kWForced) v = (uint32_t)f;
+    r.w[x] = v;
+  }
+  for (int t = tid; t < r.row_len; t += 256) {
+    if (t < f) r.out[t] = t;
+    else if (t >= k) r.out[t] = -1;
+  }
+  if (tid == 0) (kind ? a.s_cnt : a.v_cnt)[h] = k;
+}
 
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+// One digit of the radix select: threshold key T = kp-th largest key among the candidates.
+__global__ __launch_bounds__(kSelThreads) void k_sel_hist(const SelArgs a, const int pass) {
+  const SelRow r = sel_row(a, blockIdx.y);
+  const uint32_t kp = r.w[kWChoose];
+  if (kp == 0) return;
+  const int64_t lo = (int64_t)r.w[kWForced] + (int64_t)blockIdx.x * a.slice_len;
+  const int64_t hi = lo + a.slice_len < a.n ? lo + a.slice_len : a.n;
+  const uint32_t prefix = r.w[kWState + 2 * pass], krem = r.w[kWState + 2 * pass + 1];
+  const int tid = threadIdx.x, lane = tid & 63;
   // 16 copies of the 256-bin histogram, copy = lane % 16 in consecutive banks: the top digits of
   // real scores crowd into a few bins, and 64 lanes adding to one address would serialise
   __shared__ uint32_t hist16[256 * 16];
   __shared__ uint32_t hist[256];
-  __shared__ uint32_t sh_prefix, sh_krem;
-  __shared__ uint32_t wtot[2][kSelWaves][2];
-
-  for (int t = tid; t < row_len; t += kSelThreads) {
-    if (t < f) out[t] = t;
-    else if (t >= k) out[t] = -1;
+  __shared__ bool last;
+  const int shift = 24 - 8 * pass;
+  const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+  for (int x = tid; x < 256 * 16; x += kSelThreads) hist16[x] = 0;
+  __syncthreads();
+  // kSelItems independent loads per thread in flight (the pass is latency-bound otherwise)
+  for (int64_t base = lo; base < hi; base += kSelStep) {
+    uint32_t key[kSelItems];
+    bool ok[kSelItems];
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e) {
+      const int64_t i = base + (int64_t)e * kSelThreads + tid;
+      ok[e] = i < hi;
+      key[e] = order_key(r.sc[ok[e] ? i : hi - 1]);  // unconditional, so that the loads overlap
+    }
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e)
+      if (ok[e] && (key[e] & himask) == prefix)
+        atomicAdd(&hist16[(((key[e] >> shift) & 255u) << 4) | (lane & 15)], 1u);
   }
-  if (tid == 0) (kind ? a.s_cnt : a.v_cnt)[h] = k;
+  __syncthreads();
+  uint32_t* const gh = r.w + kWHist + 256 * pass;
+  // The additions and the ticket are device-wide atomics, performed where all workgroups see
+  // them.  The additions return a value, and the wait for it is the wait for their completion;
+  // only then does the workgroup draw its ticket, so the one that draws the last ticket finds
+  // every addition done.  (No cache is involved: a fence would write back the whole L2.)
+  if (tid < 256) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) c += hist16[(tid << 4) | x];
+    uint32_t old = 0;
+    if (c) old = __hip_atomic_fetch_add(&gh[tid], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
+  }
+  __syncthreads();
+  if (tid == 0)
+    last = __hip_atomic_fetch_add(&r.w[kWDone + pass], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
+  __syncthreads();
+  if (!last) return;
+  if (tid < 256) hist[tid] = __hip_atomic_load(&gh[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t cum = 0;
+    int b = 255;
+    for (; b > 0; --b) {
+      const uint32_t c = hist[b];
+      if (cum + c >= krem) break;
+      cum += c;
+    }
+    r.w[kWState + 2 * (pass + 1)] = prefix | ((uint32_t)b << shift);
+    r.w[kWState + 2 * (pass + 1) + 1] = krem - cum;
+  }
+}
+
+// Keys above and equal to the threshold in every slice.
+__global__ __launch_bounds__(kSelThreads) void k_sel_count(const SelArgs a) {
+  const SelRow r = sel_row(a, blockIdx.y);
+  if (r.w[kWChoose] == 0) return;
+  const int64_t lo = (int64_t)r.w[kWForced] + (int64_t)blockIdx.x * a.slice_len;
+  const int64_t hi = lo + a.slice_len < a.n ? lo + a.slice_len : a.n;
+  const uint32_t T = r.w[kWState + 8];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ uint32_t wtot[kSelWaves][2];
+  uint32_t tg = 0, te = 0;
+  for (int64_t base = lo; base < hi; base += kSelStep) {
+    uint32_t key[kSelItems];
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e) {
+      const int64_t i = base + (int64_t)e * kSelThreads + tid;
+      key[e] = order_key(r.sc[i < hi ? i : hi - 1]);
+    }
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e) {
+      const bool in = base + (int64_t)e * kSelThreads + tid < hi;
+      tg += __popcll(__ballot(in && key[e] > T));
+      te += __popcll(__ballot(in && key[e] == T));
+    }
+  }
+  if (lane == 0) { wtot[wv][0] = tg; wtot[wv][1] = te; }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t g = 0, e = 0;
+    for (int w = 0; w < kSelWaves; ++w) { g += wtot[w][0]; e += wtot[w][1]; }
+    r.w[kWCount + 2 * blockIdx.x] = g;
+    r.w[kWCount + 2 * blockIdx.x + 1] = e;
+  }
+}
+
+// Ordered compaction of one slice.
+__global__ __launch_bounds__(kSelThreads) void k_sel_write(const SelArgs a) {
+  const SelRow r = sel_row(a, blockIdx.y);
+  const uint32_t kp = r.w[kWChoose];
   if (kp == 0) return;
-
-  // ---- radix select: threshold key T = kp-th largest key among candidates ------------------
-  uint32_t prefix = 0, krem = (uint32_t)kp;
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    const uint32_t himask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-    for (int x = tid; x < 256 * 16; x += kSelThreads) hist16[x] = 0;
-    __syncthreads();
-    // kSelItems independent loads per thread in flight (the pass is latency-bound otherwise)
-    for (int64_t base = f; base < n; base += (int64_t)kSelThreads * kSelItems) {
-      uint32_t key[kSelItems];
-      bool ok[kSelItems];
-#pragma unroll
-      for (int e = 0; e < kSelItems; ++e) {
-        const int64_t i = base + (int64_t)e * kSelThreads + tid;
-        ok[e] = i < n;
-        key[e] = ok[e] ? order_key(sc[i]) : 0u;
-      }
-#pragma unroll
-      for (int e = 0; e < kSelItems; ++e)
-        if (ok[e] && (key[e] & himask) == prefix)
-          atomicAdd(&hist16[(((key[e] >> shift) & 255u) << 4) | (lane & 15)], 1u);
-    }
-    __syncthreads();
-    if (tid < 256) {
-      uint32_t c = 0;
-#pragma unroll
-      for (int x = 0; x < 16; ++x) c += hist16[(tid << 4) | x];
-      hist[tid] = c;
-    }
-    __syncthreads();
-    if (tid == 0) {
-      uint32_t cum = 0;
-      int b = 255;
-      for (; b > 0; --b) {
-        const uint32_t c = hist[b];
-        if (cum + c >= krem) break;
-        cum += c;
-      }
-      sh_prefix = prefix | ((uint32_t)b << shift);
-      sh_krem = krem - cum;
-    }
-    __syncthreads();
-    prefix = sh_prefix;
-    krem = sh_krem;
+  const int f = (int)r.w[kWForced];
+  const int64_t lo = (int64_t)f + (int64_t)blockIdx.x * a.slice_len;
+  const int64_t hi = lo + a.slice_len < a.n ? lo + a.slice_len : a.n;
+  const uint32_t T = r.w[kWState + 8];
+  const uint32_t need_eq = r.w[kWState + 9];  // >= 1
+  int32_t* const out = r.out;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ uint32_t wtot[2][kSelWaves][2];
+  uint32_t run_gt = 0, run_eq = 0;  // totals over everything before this slice, then before the step
+  for (int sl = 0; sl < (int)blockIdx.x; ++sl) {
+    run_gt += r.w[kWCount + 2 * sl];
+    run_eq += r.w[kWCount + 2 * sl + 1];
   }
-  const uint32_t T = prefix;
-  const uint32_t need_eq = krem;  // >= 1
-
-  // ---- ordered compaction -------------------------------------------------------------------
-  uint32_t run_gt = 0, run_eq = 0;  // totals over the chunks already done
+  if (run_gt + (run_eq < need_eq ? run_eq : need_eq) >= kp) return;  // the row is complete already
   const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
   int par = 0;
-  for (int64_t base = f; base < n; base += (int64_t)kSelThreads * kSelItems, par ^= 1) {
+  for (int64_t base = lo; base < hi; base += kSelStep, par ^= 1) {
     uint64_t bg[kSelItems], be[kSelItems];
-    uint32_t tg = 0, te = 0;
+    uint32_t tg = 0, te = 0, keys[kSelItems];
 #pragma unroll
     for (int e = 0; e < kSelItems; ++e) {
       const int64_t i = base + (int64_t)wv * (64 * kSelItems) + e * 64 + lane;
-      uint32_t key = 0;
-      if (i < n) key = order_key(sc[i]);
-      bg[e] = __ballot(i < n && key > T);
-      be[e] = __ballot(i < n && key == T);
+      keys[e] = order_key(r.sc[i < hi ? i : hi - 1]);
+    }
+#pragma unroll
+    for (int e = 0; e < kSelItems; ++e) {
+      const int64_t i = base + (int64_t)wv * (64 * kSelItems) + e * 64 + lane;
+      const uint32_t key = keys[e];
+      bg[e] = __ballot(i < hi && key > T);
+      be[e] = __ballot(i < hi && key == T);
       tg += __popcll(bg[e]);
       te += __popcll(be[e]);
     }
@@ -152,23 +255,38 @@ __global__ __launch_bounds__(kSelThreads) void k_select(const SelArgs a) {
     }
     run_gt += cg;
     run_eq += ce;
-    if (run_gt + (run_eq < need_eq ? run_eq : need_eq) >= (uint32_t)kp) break;
+    if (run_gt + (run_eq < need_eq ? run_eq : need_eq) >= kp) break;
   }
 }
 
-size_t select_ws_bytes(const vs_params&) { return 0; }
+size_t select_ws_bytes(const vs_params& p) {
+  return align_up((size_t)2 * p.n_q_heads * kSelRowWords * sizeof(uint32_t), 256);
+}
 
 hipError_t launch_select(const vs_params& p, const float* vscore, const float* sscore,
                          const int32_t* v_budget_h, const int32_t* s_budget_h,
-                         int32_t* v_idx, int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void*,
+                         int32_t* v_idx, int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void* ws,
                          hipStream_t st) {
   SelArgs a;
   a.vscore = vscore; a.sscore = sscore; a.n = p.q_start + p.q_len;
+  a.n_q_heads = p.n_q_heads;
   a.v_budget = p.vertical_budget; a.s_budget = p.slash_budget;
   a.keep_v = p.keep_first_cols; a.keep_s = p.keep_local_band;
   a.v_budget_h = v_budget_h; a.s_budget_h = s_budget_h;
   a.v_idx = v_idx; a.v_cnt = v_cnt; a.s_idx = s_idx; a.s_cnt = s_cnt;
-  hipLaunchKernelGGL(k_select, dim3(p.n_q_heads, 2), dim3(kSelThreads), 0, st, a);
+  a.ws = (uint32_t*)ws;
+  // slices: whole steps of the workgroup, enough of them for about 2048 workgroups in all
+  const int rows = 2 * p.n_q_heads;
+  int64_t want = 2048 / rows;
+  want = want < 1 ? 1 : (want > kSelMaxSlices ? kSelMaxSlices : want);
+  const int64_t steps = ceil_div(a.n, kSelStep);
+  a.slice_len = ceil_div(steps, want) * kSelStep;
+  const int n_slices = (int)ceil_div(a.n, a.slice_len);
+  const dim3 grid(n_slices, rows);
+  hipLaunchKernelGGL(k_sel_init, dim3(rows), dim3(256), 0, st, a);
+  for (int pass = 0; pass < 4; ++pass) hipLaunchKernelGGL(k_sel_hist, grid, dim3(kSelThreads), 0, st, a, pass);
+  hipLaunchKernelGGL(k_sel_count, grid, dim3(kSelThreads), 0, st, a);
+  hipLaunchKernelGGL(k_sel_write, grid, dim3(kSelThreads), 0, st, a);
   return hipGetLastError();
 }
 

@@ -42,7 +42,9 @@ def test_estimate_matches_oracle(hq, hkv, d, c, s, w):
 
 
 @pytest.mark.parametrize("n,bv,bs,kf,kb,hq", [(4096, 128, 256, 1, 64, 4), (1000, 37, 90, 0, 0, 3), (70000, 1000, 6096, 1, 64, 2),
-                                              (50, 128, 256, 1, 64, 2), (9000, 9000, 1, 3, 5, 2)])
+                                              (50, 128, 256, 1, 64, 2), (9000, 9000, 1, 3, 5, 2),
+                                              (70000, 30000, 20000, 1, 64, 2),    # ties and counts that span several slices of a row
+                                              (600000, 1000, 6096, 1, 64, 40)])  # slices longer than one step
 def test_select_is_exact_on_given_scores(n, bv, bs, kf, kb, hq):
     # same fp32 scores on both sides: the kept sets must be identical, ties to the lower index
     rng = np.random.default_rng(500 + n)
