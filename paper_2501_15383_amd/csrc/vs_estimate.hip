@@ -4,17 +4,20 @@
 // over all n_k keys, summed along columns (vscore) and along diagonals pos - j (sscore).
 //
 // Two sweeps over the K cache, both tiled the same way: a workgroup owns one KV head and a
-// contiguous range of keys; its waves are the query heads of that KV group, so every K
-// tile is fetched from HBM once per sweep for all heads of the group and staged in LDS.
+// contiguous range of keys; a wave is (query head of that KV group, half of the window rows),
+// so every K tile is fetched from HBM once per sweep for all heads of the group and staged
+// in LDS (two buffers, one barrier per tile).
 //   sweep A  per-row running (max, sum) over the range -> partials -> k_estimate_combine -> lse
-//   sweep B  P = exp2(S * scale*log2e - lse2); column sums are stored directly (a column
-//            belongs to exactly one workgroup); the diagonal sums of every 32 x 32 block come
-//            from lane rotations, are collected in an LDS strip private to the wave, and the
-//            strip is added to the zero-filled global array at the end (at most two
-//            workgroups touch one offset, and x + y is commutative), so scores are
+//   sweep B  P = exp2(S * scale*log2e - lse2).  Column sums: the wave of the upper half hands
+//            its sums to the wave of the lower half through LDS, which stores them (a column
+//            belongs to exactly one workgroup).  Diagonal sums of every 32 x 32 block come
+//            from lane rotations and are collected in an LDS strip private to the wave; the
+//            two strips of a head are added to the zero-filled global array at the end (at
+//            most two workgroups touch one offset, and x + y is commutative), so scores are
 //            run-to-run identical.
 // bf16 MFMA (32x32x16) with fp32 accumulation; sweep A uses the K Q^T orientation (a lane
-// owns one query), sweep B the Q K^T orientation (a lane owns one key).
+// owns one query), sweep B the Q K^T orientation (a lane owns one key).  Both sweeps are
+// bound by the exponential (one per score, quarter rate), not by memory.
 #include "vs_common.h"
 
 namespace vs {
@@ -37,17 +40,21 @@ struct EstArgs {
   float scale_log2;
 };
 
-template <int D, int NW, int PASS>
-__global__ __launch_bounds__(64 * NW) void k_estimate(const EstArgs a) {
-  constexpr int NT = 64 * NW, KS = D + 8, DCH = D / 8, DSTEPS = D / 16;
+template <int D, int NH, int PASS>
+__global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
+  constexpr int NW = 2 * NH, NT = 64 * NW, KS = D + 8, DCH = D / 8, DSTEPS = D / 16;
   constexpr int KPT = (64 * DCH + NT - 1) / NT;
   constexpr int STRIP = kEstRange + 64;
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[64 * KS];
+  __shared__ __attribute__((aligned(16))) __bf16 Ks[2][64 * KS];
   __shared__ float strip[PASS == 1 ? NW * STRIP : 1];
+  __shared__ float colbuf[PASS == 1 ? 2 * NH * 64 : 1];
+  __shared__ __attribute__((aligned(16))) float lse_s[PASS == 1 ? NH * 64 : 4];
 
   const int rng = blockIdx.x, g = blockIdx.y, hb = blockIdx.z;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, hh = lane >> 5;
-  const int hin = hb * NW + wv;
+  const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hw = wv >> 1, ib = wv & 1;  // head inside the workgroup, half of the window rows
+  const int hin = hb * NH + hw;
   const bool head_ok = hin < a.group;
   const int h = g * a.group + (head_ok ? hin : 0);
   const int64_t ja = (int64_t)rng * kEstRange;
@@ -55,39 +62,36 @@ __global__ __launch_bounds__(64 * NW) void k_estimate(const EstArgs a) {
   const int n_tiles = (int)((jb_ - ja + 63) >> 6);
   const __bf16* kbase = a.k + (int64_t)g * a.k_stride_head;
 
-  // window rows of this head, as MFMA operand: lane (r = 32 ib + lane%32, hh)
-  bf16x8 qreg[2][DSTEPS];
-#pragma unroll
-  for (int ib = 0; ib < 2; ++ib) {
+  // window rows of this wave, as MFMA operand: lane (r = 32 ib + lane%32, hh)
+  bf16x8 qreg[DSTEPS];
+  {
     int r = 32 * ib + (lane & 31);
     if (r > a.wp - 1) r = a.wp - 1;
     const __bf16* qp = a.q + (a.q_len - a.wp + r) * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
 #pragma unroll
-    for (int st = 0; st < DSTEPS; ++st) qreg[ib][st] = *(const bf16x8*)(qp + 16 * st);
+    for (int st = 0; st < DSTEPS; ++st) qreg[st] = *(const bf16x8*)(qp + 16 * st);
   }
 
+  float* const my_strip = &strip[PASS == 1 ? wv * STRIP : 0];
   if (PASS == 1) {
     for (int x = tid; x < NW * STRIP; x += NT) strip[x] = 0.f;
   }
 
   // sweep A state: this lane's (max, sum) for query 32 ib + lane%32 over its half of the keys
-  float mrun[2] = {-INFINITY, -INFINITY}, lrun[2] = {0.f, 0.f};
-  // sweep B: lse2 of the 32 queries this lane meets: i = 32 ib + 8 (x/4) + 4 hh + (x%4)
-  float lse_r[2][16];
+  float mrun = -INFINITY, lrun = 0.f;
+  // sweep B: lse2 of the head's window rows; a lane meets queries 32 ib + 8 (x/4) + 4 hh + (x%4)
   if (PASS == 1) {
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib)
-#pragma unroll
-      for (int x = 0; x < 16; ++x)
-        lse_r[ib][x] = a.lse2[(int64_t)h * 64 + 32 * ib + 8 * (x >> 2) + 4 * hh + (x & 3)];
+    if (ib == 0) lse_s[hw * 64 + lane] = a.lse2[(int64_t)h * 64 + lane];
   }
+  const f32x4* const lse_q = (const f32x4*)&lse_s[PASS == 1 ? hw * 64 + 32 * ib + 4 * hh : 0];
+  float col_prev = 0.f;  // sweep B, lower half: own column sum of the previous tile, column `lane`
 
   u32x4 kst[KPT];
   auto load_tile = [&](int tile) {
 #pragma unroll
     for (int e = 0; e < KPT; ++e) {
       const int x = tid + e * NT;
-      if (x < 64 * DCH) {
+      if (KPT * NT == 64 * DCH || x < 64 * DCH) {
         const int r = x / DCH, ch = x % DCH;
         int64_t j = ja + 64 * tile + r;
         if (j > a.n_k - 1) j = a.n_k - 1;
@@ -95,132 +99,144 @@ __global__ __launch_bounds__(64 * NW) void k_estimate(const EstArgs a) {
       }
     }
   };
-  auto store_tile = [&]() {
+  auto store_tile = [&](int buf) {
 #pragma unroll
     for (int e = 0; e < KPT; ++e) {
       const int x = tid + e * NT;
-      if (x < 64 * DCH) {
+      if (KPT * NT == 64 * DCH || x < 64 * DCH) {
         const int r = x / DCH, ch = x % DCH;
-        *(u32x4*)&Ks[r * KS + ch * 8] = kst[e];
+        *(u32x4*)&Ks[buf][r * KS + ch * 8] = kst[e];
       }
     }
   };
+  // column sums of tile `tile` of this head: own half in col_prev, the other half in colbuf
+  auto flush_columns = [&](int tile) {
+    const int64_t j = ja + 64 * tile + lane;
+    const float other = colbuf[((tile & 1) * NH + hw) * 64 + lane];
+    if (j < a.n_k) a.vscore[(int64_t)h * a.n_k + j] = col_prev + other;
+  };
 
   load_tile(0);
+  store_tile(0);
+  __syncthreads();
   for (int tile = 0; tile < n_tiles; ++tile) {
-    store_tile();
-    __syncthreads();
+    const int buf = tile & 1;
     if (tile + 1 < n_tiles) load_tile(tile + 1);
     const int64_t j0 = ja + 64 * tile;
     const bool need_mask = j0 + 63 > a.p0;  // some (row, key) of this tile is acausal
 
     if (head_ok) {
+      if (PASS == 1 && ib == 0 && tile > 0) flush_columns(tile - 1);
+      float col[2];
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
-        bf16x8 kf[DSTEPS];
+        const __bf16* const kfp = &Ks[buf][(32 * jb + (lane & 31)) * KS + 8 * hh];
+        f32x16 s;
 #pragma unroll
-        for (int st = 0; st < DSTEPS; ++st)
-          kf[st] = *(const bf16x8*)&Ks[(32 * jb + (lane & 31)) * KS + 16 * st + 8 * hh];
-        float colacc = 0.f;  // sweep B: this lane's column sum over both query halves
+        for (int x = 0; x < 16; ++x) s[x] = 0.f;
+        if (PASS == 0) {
+          // D[j][i]: lane = query i, element x = key 32 jb + 8 (x/4) + 4 hh + (x%4)
 #pragma unroll
-        for (int ib = 0; ib < 2; ++ib) {
-          f32x16 s;
-#pragma unroll
-          for (int x = 0; x < 16; ++x) s[x] = 0.f;
-          if (PASS == 0) {
-            // D[j][i]: lane = query i, element x = key 32 jb + 8 (x/4) + 4 hh + (x%4)
-#pragma unroll
-            for (int st = 0; st < DSTEPS; ++st)
-              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[st], qreg[ib][st], s, 0, 0, 0);
-            const int r = 32 * ib + (lane & 31);
-            if (need_mask) {
-#pragma unroll
-              for (int x = 0; x < 16; ++x) {
-                const int64_t j = j0 + 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-                if (j > a.p0 + r) s[x] = -INFINITY;
-              }
-            }
-            float mx = s[0];
-#pragma unroll
-            for (int x = 1; x < 16; ++x) mx = fmaxf(mx, s[x]);
-            const float m_new = fmaxf(mrun[ib], mx * a.scale_log2);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            float acc = lrun[ib] * __builtin_amdgcn_exp2f(mrun[ib] - m_use);
+          for (int st = 0; st < DSTEPS; ++st)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], s, 0, 0, 0);
+          if (need_mask) {
+            // key j is masked for query r iff j - p0 > r; dr = r - (j0 - p0) - 32 jb - 4 hh
+            const int dr = 32 * ib + (lane & 31) - (int)(j0 - a.p0) - 32 * jb - 4 * hh;
 #pragma unroll
             for (int x = 0; x < 16; ++x)
-              acc += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -m_use));
-            lrun[ib] = acc;
-            mrun[ib] = m_new;
-          } else {
-            // D[i][j]: lane = key j = 32 jb + lane%32, element x = query 32 ib + 8 (x/4) + 4 hh + (x%4)
-#pragma unroll
-            for (int st = 0; st < DSTEPS; ++st)
-              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[ib][st], kf[st], s, 0, 0, 0);
-            const int jl = 64 * tile + 32 * jb + (lane & 31);  // key index inside the range
-            const int64_t j = ja + jl;
-            // Diagonal sums of this 32 x 32 block without atomics.  Element x of a lane is
-            // query q = 8 (x/4) + 4 hh + (x%4) of the block against key t = lane % 32, on block
-            // diagonal e = q - t.  Rotating the 32-lane vector of element x by q lanes (inside
-            // each half-wave) puts e = -t (no wrap) or e = 32 - t (wrapped) into lane t for
-            // every x, so two accumulators per lane collect all 63 diagonals of the block.
-            float colsum = 0.f, dneg = 0.f, dpos = 0.f;
-            const int t4 = (lane & 31) + 4 * hh;
-#pragma unroll
-            for (int x = 0; x < 16; ++x) {
-              const int q0 = 8 * (x >> 2) + (x & 3);
-              const int i = 32 * ib + q0 + 4 * hh;
-              float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -lse_r[ib][x]));
-              if (need_mask && j > a.p0 + i) p = 0.f;
-              colsum += p;
-              const int src = ((t4 + q0) & 31) | (lane & 32);
-              const float r = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, p)));
-              const bool wrapped = t4 + q0 >= 32;
-              dneg += wrapped ? 0.f : r;
-              dpos += wrapped ? r : 0.f;
-            }
-            dneg += __shfl_xor(dneg, 32);
-            dpos += __shfl_xor(dpos, 32);
-            // strip index of (query i, key jl) is i - jl + (kEstRange - 1); the strip is private
-            // to the wave and the 32 addresses of one update are distinct
-            if (hh == 0) {
-              float* sp = &strip[wv * STRIP + 32 * (ib - jb) - 64 * tile + (kEstRange - 1) - (lane & 31)];
-              sp[0] += dneg;
-              if ((lane & 31) != 0) sp[32] += dpos;
-            }
-            colacc += colsum;
+              if (8 * (x >> 2) + (x & 3) > dr) s[x] = -INFINITY;
           }
-        }
-        if (PASS == 1) {
-          colacc += __shfl_xor(colacc, 32);
-          const int64_t j = ja + 64 * tile + 32 * jb + (lane & 31);
-          if (hh == 0 && j < a.n_k) a.vscore[(int64_t)h * a.n_k + j] = colacc;
+          float mx = s[0];
+#pragma unroll
+          for (int x = 1; x < 16; ++x) mx = fmaxf(mx, s[x]);
+          const float m_new = fmaxf(mrun, mx * a.scale_log2);
+          const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+          float acc = lrun * __builtin_amdgcn_exp2f(mrun - m_use);
+#pragma unroll
+          for (int x = 0; x < 16; ++x)
+            acc += __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -m_use));
+          lrun = acc;
+          mrun = m_new;
+        } else {
+          // D[i][j]: lane = key j = 32 jb + lane%32, element x = query 32 ib + 8 (x/4) + 4 hh + (x%4)
+#pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            // K operands in two batches, so that only half of them are live at a time
+            bf16x8 kf[DSTEPS / 2];
+#pragma unroll
+            for (int st = 0; st < DSTEPS / 2; ++st) kf[st] = *(const bf16x8*)(kfp + 16 * (st + half * (DSTEPS / 2)));
+#pragma unroll
+            for (int st = 0; st < DSTEPS / 2; ++st)
+              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[st + half * (DSTEPS / 2)], kf[st], s, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          // causal mask in 32 bits: key j is masked for query i iff j - p0 > i; dj = j - p0 - 4 hh
+          // is compared with the uniform 32 ib + q0 (only tiles at the end of the keys need it)
+          const int dj = need_mask ? (int)(j0 - a.p0) + 32 * jb + (lane & 31) - 4 * hh : 0;
+          // Diagonal sums of this 32 x 32 block without atomics.  Element x of a lane is
+          // query q = 8 (x/4) + 4 hh + (x%4) of the block against key t = lane % 32, on block
+          // diagonal e = q - t.  Rotating the 32-lane vector of element x by q lanes (inside
+          // each half-wave) puts e = -t (no wrap) or e = 32 - t (wrapped) into lane t for
+          // every x, so two accumulators per lane collect all 63 diagonals of the block.
+          float colsum = 0.f, dneg = 0.f, dpos = 0.f;
+          const int t4 = (lane & 31) + 4 * hh;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            const int q0 = 8 * (x >> 2) + (x & 3);
+            const f32x4 lse4 = lse_q[2 * (x >> 2)];
+            float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -lse4[x & 3]));
+            if (need_mask && dj > 32 * ib + q0) p = 0.f;
+            colsum += p;
+            const int src = ((t4 + q0) & 31) | (lane & 32);
+            const float r = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, p)));
+            const bool wrapped = t4 + q0 >= 32;
+            dneg += wrapped ? 0.f : r;
+            dpos += wrapped ? r : 0.f;
+          }
+          dneg += __shfl_xor(dneg, 32);
+          dpos += __shfl_xor(dpos, 32);
+          // strip index of (query i, key jl) is i - jl + (kEstRange - 1); the strip is private
+          // to the wave and the 32 addresses of one update are distinct
+          if (hh == 0) {
+            float* sp = &my_strip[32 * (ib - jb) - 64 * tile + (kEstRange - 1) - (lane & 31)];
+            sp[0] += dneg;
+            if ((lane & 31) != 0) sp[32] += dpos;
+          }
+          col[jb] = colsum + __shfl_xor(colsum, 32);
         }
       }
+      if (PASS == 1) {
+        // every lane now has the sums of columns lane%32 (jb = 0) and 32 + lane%32 (jb = 1)
+        const float mine = hh ? col[1] : col[0];  // column `lane` of the tile
+        if (ib == 1) colbuf[(buf * NH + hw) * 64 + lane] = mine;
+        else col_prev = mine;
+      }
     }
+    if (tile + 1 < n_tiles) store_tile(buf ^ 1);
     __syncthreads();
   }
 
   if (!head_ok) return;
   if (PASS == 0) {
     // merge the two key halves of each query, then one partial per (head, range, row)
-#pragma unroll
-    for (int ib = 0; ib < 2; ++ib) {
-      const float m2 = __shfl_xor(mrun[ib], 32), l2 = __shfl_xor(lrun[ib], 32);
-      const float M = fmaxf(mrun[ib], m2);
-      const float Mu = (M == -INFINITY) ? 0.f : M;
-      const float L = lrun[ib] * __builtin_amdgcn_exp2f(mrun[ib] - Mu) + l2 * __builtin_amdgcn_exp2f(m2 - Mu);
-      if (hh == 0) {
-        float* pp = a.part + (((int64_t)h * a.n_ranges + rng) * 64 + 32 * ib + (lane & 31)) * 2;
-        pp[0] = M;
-        pp[1] = L;
-      }
+    const float m2 = __shfl_xor(mrun, 32), l2 = __shfl_xor(lrun, 32);
+    const float M = fmaxf(mrun, m2);
+    const float Mu = (M == -INFINITY) ? 0.f : M;
+    const float L = lrun * __builtin_amdgcn_exp2f(mrun - Mu) + l2 * __builtin_amdgcn_exp2f(m2 - Mu);
+    if (hh == 0) {
+      float* pp = a.part + (((int64_t)h * a.n_ranges + rng) * 64 + 32 * ib + (lane & 31)) * 2;
+      pp[0] = M;
+      pp[1] = L;
     }
   } else {
-    // strip index x <-> offset o = p0 - ja - (kEstRange - 1) + x
+    if (ib == 0) flush_columns(n_tiles - 1);
+    // the two strips of the head, added; strip index x <-> offset o = p0 - ja - (kEstRange - 1) + x
+    const float* s0 = &strip[(2 * hw) * STRIP];
+    const float* s1 = s0 + STRIP;
     const int64_t o0 = a.p0 - ja - (kEstRange - 1);
-    for (int x = lane; x < STRIP; x += 64) {
+    for (int x = lane + 64 * ib; x < STRIP; x += 128) {
       const int64_t o = o0 + x;
-      const float val = strip[wv * STRIP + x];
+      const float val = s0[x] + s1[x];
       if (o >= 0 && o < a.n_k && val != 0.f) atomicAdd(&a.sscore[(int64_t)h * a.n_k + o], val);
     }
   }
@@ -257,6 +273,7 @@ __global__ __launch_bounds__(256) void k_fill_zero(float* p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
 }
 
+// heads per workgroup (two waves each)
 static int pick_waves(int group) {
   const int cand[] = {1, 2, 4, 5, 7, 8};
   for (int c : cand)
@@ -271,12 +288,12 @@ size_t estimate_ws_bytes(const vs_params& p) {
          align_up((size_t)p.n_q_heads * 64 * sizeof(float), 256);
 }
 
-template <int D, int NW>
+template <int D, int NH>
 static hipError_t launch_est(const EstArgs& a, int hb, hipStream_t st) {
   const dim3 grid(a.n_ranges, a.n_kv_heads, hb);
-  hipLaunchKernelGGL((k_estimate<D, NW, 0>), grid, dim3(64 * NW), 0, st, a);
+  hipLaunchKernelGGL((k_estimate<D, NH, 0>), grid, dim3(128 * NH), 0, st, a);
   hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(1024), 0, st, a);
-  hipLaunchKernelGGL((k_estimate<D, NW, 1>), grid, dim3(64 * NW), 0, st, a);
+  hipLaunchKernelGGL((k_estimate<D, NH, 1>), grid, dim3(128 * NH), 0, st, a);
   return hipGetLastError();
 }
 
