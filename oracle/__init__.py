@@ -145,11 +145,38 @@ def select_heads(pb: Problem, vscore, sscore, v_budget, s_budget):
     return v_idx, v_cnt, s_idx, s_cnt
 
 
-def estimate(pb: Problem, q, k, heads=None):
+@dataclass
+class Dca:
+    """Dual Chunk Attention (section 5.1): chunk length, local window and the two other
+    rotations of the chunk's queries (u16 [C][Hq][D] each); q itself is the intra-chunk one."""
+    chunk: int
+    window: int
+    q_succ: np.ndarray
+    q_inter: np.ndarray
+
+
+def dca_region(pos_q: int, pos_k: int, chunk: int, window: int) -> int:
+    """0 intra-chunk, 1 successive-chunk (inside the local window), 2 inter-chunk."""
+    return int(lib().vso_dca_region(C.c_int64(pos_q), C.c_int64(pos_k), C.c_int64(chunk), C.c_int64(window)))
+
+
+def estimate(pb: Problem, q, k, heads=None, dca: Dca | None = None):
     """Step 1.  q: [C][Hq][D] u16 (the chunk), k: [>=n_k][Hkv][D] u16.
     Returns vscore [nh][n_k], sscore [nh][n_k], lse_lastq [nh][W'] (fp64)."""
     q = _u16(q, (pb.n_q_heads, pb.head_dim)); k = _u16(k, (pb.n_kv_heads, pb.head_dim))
     assert q.shape[0] == pb.q_len and k.shape[0] >= pb.n_k
+    if dca is not None:
+        qs = _u16(dca.q_succ, (pb.n_q_heads, pb.head_dim)); qi = _u16(dca.q_inter, (pb.n_q_heads, pb.head_dim))
+        assert qs.shape == q.shape and qi.shape == q.shape and dca.chunk > 0 and dca.window >= 0
+        heads = np.arange(pb.n_q_heads, dtype=np.int32) if heads is None else np.asarray(heads, np.int32)
+        wp = min(pb.last_q, pb.q_len)
+        vs = np.zeros((len(heads), pb.n_k)); ss = np.zeros((len(heads), pb.n_k)); lse = np.zeros((len(heads), wp))
+        prm = pb._c()
+        rc = lib().vso_estimate_dca(C.byref(prm), _p(q, C.c_uint16), _p(qs, C.c_uint16), _p(qi, C.c_uint16),
+                                    C.c_int64(dca.chunk), C.c_int64(dca.window), _p(k, C.c_uint16), len(heads),
+                                    _p(heads, C.c_int32), _p(vs, C.c_double), _p(ss, C.c_double), _p(lse, C.c_double))
+        assert rc == 0
+        return vs, ss, lse
     heads = np.arange(pb.n_q_heads, dtype=np.int32) if heads is None else np.asarray(heads, np.int32)
     wp = min(pb.last_q, pb.q_len)
     vs = np.zeros((len(heads), pb.n_k)); ss = np.zeros((len(heads), pb.n_k))
@@ -202,7 +229,7 @@ def mask(pb: Problem, v_idx, s_idx, rows=None):
     return m
 
 
-def _attention(pb, q, k, v, sets, heads, rows):
+def _attention(pb, q, k, v, sets, heads, rows, dca=None):
     q = _u16(q, (pb.n_q_heads, pb.head_dim)); k = _u16(k, (pb.n_kv_heads, pb.head_dim))
     v = _u16(v, (pb.n_kv_heads, pb.head_dim))
     assert q.shape[0] == pb.q_len and k.shape[0] >= pb.n_k and v.shape[0] >= pb.n_k
@@ -218,21 +245,27 @@ def _attention(pb, q, k, v, sets, heads, rows):
         assert v_idx.shape == (pb.n_q_heads, pb.vertical_budget)
         assert s_idx.shape == (pb.n_q_heads, pb.slash_budget)
         a = (v_idx, v_cnt, s_idx, s_cnt)
-    rc = lib().vso_attention(C.byref(prm), _p(q, C.c_uint16), _p(k, C.c_uint16), _p(v, C.c_uint16),
-                             _p(a[0], C.c_int32), _p(a[1], C.c_int32), _p(a[2], C.c_int32),
-                             _p(a[3], C.c_int32), len(heads), _p(heads, C.c_int32),
-                             C.c_int64(len(rows)), _p(rows, C.c_int64),
-                             _p(out, C.c_double), _p(lse, C.c_double))
+    tail = (_p(a[0], C.c_int32), _p(a[1], C.c_int32), _p(a[2], C.c_int32),
+            _p(a[3], C.c_int32), len(heads), _p(heads, C.c_int32),
+            C.c_int64(len(rows)), _p(rows, C.c_int64), _p(out, C.c_double), _p(lse, C.c_double))
+    if dca is None:
+        rc = lib().vso_attention(C.byref(prm), _p(q, C.c_uint16), _p(k, C.c_uint16), _p(v, C.c_uint16), *tail)
+    else:
+        qs = _u16(dca.q_succ, (pb.n_q_heads, pb.head_dim)); qi = _u16(dca.q_inter, (pb.n_q_heads, pb.head_dim))
+        assert qs.shape == q.shape and qi.shape == q.shape and dca.chunk > 0 and dca.window >= 0
+        rc = lib().vso_attention_dca(C.byref(prm), _p(q, C.c_uint16), _p(qs, C.c_uint16), _p(qi, C.c_uint16),
+                                     C.c_int64(dca.chunk), C.c_int64(dca.window), _p(k, C.c_uint16),
+                                     _p(v, C.c_uint16), *tail)
     assert rc == 0
     return out, lse
 
 
-def sparse_attention(pb: Problem, q, k, v, v_idx, v_cnt, s_idx, s_cnt, heads=None, rows=None):
+def sparse_attention(pb: Problem, q, k, v, v_idx, v_cnt, s_idx, s_cnt, heads=None, rows=None, dca: Dca | None = None):
     """Step 3.  Index sets are [Hq][Bv] / [Hq][Bs] for ALL heads; ``heads``/``rows``
     pick which outputs are computed.  Returns out [nh][nr][D], lse [nh][nr] (fp64)."""
-    return _attention(pb, q, k, v, (v_idx, v_cnt, s_idx, s_cnt), heads, rows)
+    return _attention(pb, q, k, v, (v_idx, v_cnt, s_idx, s_cnt), heads, rows, dca)
 
 
-def dense_attention(pb: Problem, q, k, v, heads=None, rows=None):
+def dense_attention(pb: Problem, q, k, v, heads=None, rows=None, dca: Dca | None = None):
     """Step 4: causal softmax attention over every key j <= pos(i)."""
-    return _attention(pb, q, k, v, None, heads, rows)
+    return _attention(pb, q, k, v, None, heads, rows, dca)

@@ -6,7 +6,8 @@
  * Inference with Sparse Attention": the MInference paragraph and the
  * "Integrating with Chunked prefill" paragraph; softmax_lse and
  * Attention_Recall from the "Sparsity refinement" paragraph; attention
- * temperature from the YaRN equation of section 5.1).
+ * temperature from the YaRN equation and the three attention patterns of Dual
+ * Chunk Attention from section 5.1).
  *
  * It exists so that the GPU library can be checked against something that a
  * reader can compare with the paper by eye.  Only tests, the smoke check and the
@@ -30,7 +31,12 @@
  * Pins (tests/test_oracle_*.py): dense attention against an independent
  * brute-force softmax, closed forms at Q = 0, rows of P summing to one,
  * score conservation, hand-written tiny masks, everything-selected == dense,
- * recall in (0,1], selection against a stable sort.  Accuracy of the sparse
+ * recall in (0,1], selection against a stable sort; the Dual Chunk Attention
+ * variants against a hand-written pattern matrix, a brute force that reads its
+ * patterns from that matrix, and the cases in which they must reduce to the
+ * plain functions.  The position lists printed for the figure of "Integrating
+ * with DCA" are parity unpinned: the figure itself is missing from the text and
+ * the lists alone do not fix chunk length and window.  Accuracy of the sparse
  * result against dense attention on real text is parity unpinned (it needs
  * trained weights and the paper's evaluation suites).
  */
@@ -62,9 +68,39 @@ static double bf16_to_f64(uint16_t b) {
   return (double)f;
 }
 
-/* scale * <q_i, k_j> for query head h (kv head g). */
-static double logit(const vso_params *p, const uint16_t *q, const uint16_t *k,
-                    int64_t i, int h, int g, int64_t j) {
+/* ---------------------------------------------------------------------------
+ * Dual Chunk Attention (section 5.1, DCA paragraph): the sequence is cut into
+ * chunks of `chunk` tokens and the (query, key) pairs fall into three patterns
+ *   0 intra-chunk       query and key in the same chunk
+ *   1 successive-chunk  key in the chunk before the query's AND the distance
+ *                       pos_q - pos_k inside the local window (< window)
+ *   2 inter-chunk       every other pair
+ * Each pattern has its own rotation of the query (the remapped relative
+ * positions); the keys are stored once.  The caller supplies the three rotated
+ * query tensors; what is computed here is which of them meets which key.
+ * ------------------------------------------------------------------------- */
+typedef struct vso_dca {
+  int64_t chunk;  /* 0 = no DCA: every pair uses the first query tensor */
+  int64_t window;
+  const uint16_t *q_succ, *q_inter;
+} vso_dca;
+
+int vso_dca_region(int64_t pos_q, int64_t pos_k, int64_t chunk, int64_t window) {
+  const int64_t cq = pos_q / chunk, ck = pos_k / chunk;
+  if (cq == ck) return 0;
+  if (cq == ck + 1 && pos_q - pos_k < window) return 1;
+  return 2;
+}
+
+/* scale * <q_i, k_j> for query head h (kv head g); i is the row of the chunk,
+ * pos its absolute position. */
+static double logit(const vso_params *p, const vso_dca *dca, const uint16_t *q,
+                    const uint16_t *k, int64_t i, int h, int g, int64_t j) {
+  if (dca && dca->chunk > 0) {
+    const int r = vso_dca_region(p->q_start + i, j, dca->chunk, dca->window);
+    if (r == 1) q = dca->q_succ;
+    if (r == 2) q = dca->q_inter;
+  }
   const uint16_t *qr = q + i * p->q_stride_tok + (int64_t)h * p->q_stride_head;
   const uint16_t *kr = k + j * p->k_stride_tok + (int64_t)g * p->k_stride_head;
   double acc = 0.0;
@@ -92,9 +128,9 @@ double vso_yarn_softmax_scale(double s, int head_dim) {
  *   lse_lastq[r] = log sum_j exp(logit)
  * Outputs are [n_heads][n_k] (scores) and [n_heads][W'] (lse), fp64.
  * ------------------------------------------------------------------------- */
-int vso_estimate(const vso_params *p, const uint16_t *q, const uint16_t *k,
-                 int n_heads, const int32_t *heads, double *vscore,
-                 double *sscore, double *lse_lastq) {
+static int estimate_impl(const vso_params *p, const vso_dca *dca, const uint16_t *q,
+                         const uint16_t *k, int n_heads, const int32_t *heads,
+                         double *vscore, double *sscore, double *lse_lastq) {
   const int64_t C = p->q_len, s = p->q_start, n_k = s + C;
   const int64_t Wp = p->last_q < C ? p->last_q : C;
   const int G = p->n_q_heads / p->n_kv_heads;
@@ -109,7 +145,7 @@ int vso_estimate(const vso_params *p, const uint16_t *q, const uint16_t *k,
       double *Pr = P + r * n_k;
       double m = -INFINITY;
       for (int64_t j = 0; j <= pos; ++j) {
-        Pr[j] = logit(p, q, k, i, h, g, j);
+        Pr[j] = logit(p, dca, q, k, i, h, g, j);
         if (Pr[j] > m) m = Pr[j];
       }
       double L = 0.0;
@@ -136,6 +172,23 @@ int vso_estimate(const vso_params *p, const uint16_t *q, const uint16_t *k,
   }
   free(P);
   return 0;
+}
+
+int vso_estimate(const vso_params *p, const uint16_t *q, const uint16_t *k,
+                 int n_heads, const int32_t *heads, double *vscore,
+                 double *sscore, double *lse_lastq) {
+  return estimate_impl(p, NULL, q, k, n_heads, heads, vscore, sscore, lse_lastq);
+}
+
+/* The same with DCA: window row i meets key j through the query tensor of their
+ * pattern ("Integrating with DCA", section 5.2: the selection may be given other
+ * rotations than the attention itself; that choice is the caller's). */
+int vso_estimate_dca(const vso_params *p, const uint16_t *q_intra, const uint16_t *q_succ,
+                     const uint16_t *q_inter, int64_t chunk, int64_t window,
+                     const uint16_t *k, int n_heads, const int32_t *heads,
+                     double *vscore, double *sscore, double *lse_lastq) {
+  const vso_dca dca = {chunk, window, q_succ, q_inter};
+  return estimate_impl(p, &dca, q_intra, k, n_heads, heads, vscore, sscore, lse_lastq);
 }
 
 /* ---------------------------------------------------------------------------
@@ -255,11 +308,11 @@ int vso_mask(const vso_params *p, const int32_t *v_idx, int32_t v_cnt,
  * v_idx / s_idx are [Hq][Bv] / [Hq][Bs] indexed by the head number itself.
  * out: [n_heads][n_rows][D] fp64, lse: [n_heads][n_rows] fp64.
  * ------------------------------------------------------------------------- */
-int vso_attention(const vso_params *p, const uint16_t *q, const uint16_t *k,
-                  const uint16_t *v, const int32_t *v_idx, const int32_t *v_cnt,
-                  const int32_t *s_idx, const int32_t *s_cnt, int n_heads,
-                  const int32_t *heads, int64_t n_rows, const int64_t *rows,
-                  double *out, double *lse) {
+static int attention_impl(const vso_params *p, const vso_dca *dca, const uint16_t *q,
+                          const uint16_t *k, const uint16_t *v, const int32_t *v_idx,
+                          const int32_t *v_cnt, const int32_t *s_idx, const int32_t *s_cnt,
+                          int n_heads, const int32_t *heads, int64_t n_rows,
+                          const int64_t *rows, double *out, double *lse) {
   const int64_t n_k = p->q_start + p->q_len, n_a = n_k / p->block + 2;
   const int G = p->n_q_heads / p->n_kv_heads, D = p->head_dim;
   uint8_t *is_v = NULL, *in_a = NULL;
@@ -287,7 +340,7 @@ int vso_attention(const vso_params *p, const uint16_t *q, const uint16_t *k,
         double m = -INFINITY;
         for (int64_t j = 0; j <= pos; ++j)
           if (in_mask(p, is_v, in_a, pos, j)) {
-            x[j] = logit(p, q, k, i, h, g, j);
+            x[j] = logit(p, dca, q, k, i, h, g, j);
             if (x[j] > m) m = x[j];
           }
         for (int d = 0; d < D; ++d) o[d] = 0.0;
@@ -312,6 +365,28 @@ int vso_attention(const vso_params *p, const uint16_t *q, const uint16_t *k,
   free(is_v);
   free(in_a);
   return 0;
+}
+
+int vso_attention(const vso_params *p, const uint16_t *q, const uint16_t *k,
+                  const uint16_t *v, const int32_t *v_idx, const int32_t *v_cnt,
+                  const int32_t *s_idx, const int32_t *s_cnt, int n_heads,
+                  const int32_t *heads, int64_t n_rows, const int64_t *rows,
+                  double *out, double *lse) {
+  return attention_impl(p, NULL, q, k, v, v_idx, v_cnt, s_idx, s_cnt, n_heads, heads,
+                        n_rows, rows, out, lse);
+}
+
+/* The same with DCA: the mask is unchanged, every logit uses the query tensor of
+ * its (query, key) pattern, one softmax over all of them. */
+int vso_attention_dca(const vso_params *p, const uint16_t *q_intra, const uint16_t *q_succ,
+                      const uint16_t *q_inter, int64_t chunk, int64_t window,
+                      const uint16_t *k, const uint16_t *v, const int32_t *v_idx,
+                      const int32_t *v_cnt, const int32_t *s_idx, const int32_t *s_cnt,
+                      int n_heads, const int32_t *heads, int64_t n_rows,
+                      const int64_t *rows, double *out, double *lse) {
+  const vso_dca dca = {chunk, window, q_succ, q_inter};
+  return attention_impl(p, &dca, q_intra, k, v, v_idx, v_cnt, s_idx, s_cnt, n_heads, heads,
+                        n_rows, rows, out, lse);
 }
 
 /* Attention_Recall = exp(lse_sparse - lse_full) ("Sparsity refinement" paragraph). */
