@@ -177,6 +177,37 @@ int vs_refine_step(const vs_params *p, const float *recall, float threshold,
                    int32_t add_vertical, int32_t add_slash, int32_t *v_budget_h,
                    int32_t *s_budget_h, int32_t *changed, void *stream);
 
+/* Dual Chunk Attention (sec. 5.1, "Dual Chunk Attention" paragraph; sec. 5.2,
+ * "Integrating with DCA").  The sequence is cut into chunks of `chunk` tokens and a
+ * (query, key) pair falls into one of three patterns, each with its own remapped
+ * relative positions, i.e. its own rotation of the query against the keys as stored:
+ *   intra-chunk       query and key in the same chunk                       -> q_intra
+ *   successive-chunk  key in the chunk before the query's and
+ *                     pos_q - pos_k < window                                -> q_succ
+ *   inter-chunk       every other pair                                      -> q_inter
+ * The rotations themselves (RoPE at the remapped positions) are the caller's; the
+ * calls below choose, per pair, which of the three tensors meets the key, under one
+ * softmax.  q_succ and q_inter have the shape, strides and alignment of the q
+ * argument (device bf16 [C][Hq][D], strides of vs_params).  chunk > 0 and
+ * window >= 0 must be multiples of 64 (VS_ERR_UNSUPPORTED otherwise).  The paper
+ * selects the critical tokens with other ("continuous") relative positions than it
+ * attends with: pass the rotations made for the selection to vs_estimate_dca and
+ * those of DCA proper to the attention calls.  Everything else (masks, outputs,
+ * workspaces, errors) is as in the calls without _dca. */
+typedef struct vs_dca {
+  const void *q_succ;
+  const void *q_inter;
+  int64_t chunk;
+  int64_t window;
+} vs_dca;
+int vs_sparse_attn_prefill_dca(const vs_params *p, const void *q_intra, const vs_dca *dca,
+                               const void *k, const void *v, const int32_t *v_idx,
+                               const int32_t *v_cnt, const int32_t *s_idx, const int32_t *s_cnt,
+                               void *out, float *lse, void *ws, size_t ws_bytes, void *stream);
+int vs_dense_causal_prefill_dca(const vs_params *p, const void *q_intra, const vs_dca *dca,
+                                const void *k, const void *v, void *out, float *lse, void *ws,
+                                size_t ws_bytes, void *stream);
+
 /* Cost model and chunk planner (host functions; sec. 6.3 "Dynamic Chunked Pipeline
  * Parallelism": chunk sizes are adjusted to the complexity of the attention
  * kernel so that every chunk takes about the same time).  The unit is one 64x64

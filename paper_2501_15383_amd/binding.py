@@ -36,6 +36,11 @@ class VsParams(C.Structure):
     ]
 
 
+class VsDca(C.Structure):
+    """Mirror of `vs_dca` in include/vs.h."""
+    _fields_ = [("q_succ", C.c_void_p), ("q_inter", C.c_void_p), ("chunk", C.c_int64), ("window", C.c_int64)]
+
+
 class VsError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -91,7 +96,8 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
-           "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step"]
+           "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step",
+           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca"]
 
 
 def status_string(status: int) -> str:
@@ -273,8 +279,18 @@ def _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt):
     assert v_idx.shape == (ck.n_q_heads, ck.vertical_budget) and s_idx.shape == (ck.n_q_heads, ck.slash_budget)
 
 
-def sparse_attn_prefill(ck: Chunk, q, k, v, v_idx, v_cnt, s_idx, s_cnt, want_lse=False, out=None, ws=None):
-    """vs_sparse_attn_prefill.  Returns out bf16 [C][Hq][D] and lse fp32 [Hq][C] (or None)."""
+def _dca_struct(ck: Chunk, q, dca):
+    """dca = (q_succ, q_inter, chunk, window); the two tensors must look like q."""
+    q_succ, q_inter, chunk, window = dca
+    for t, nm in ((q_succ, "q_succ"), (q_inter, "q_inter")):
+        _chk_inner(t, nm, ck.head_dim)
+        assert t.shape == q.shape and t.stride() == q.stride() and t.device == q.device, nm
+    return VsDca(q_succ.data_ptr(), q_inter.data_ptr(), int(chunk), int(window))
+
+
+def sparse_attn_prefill(ck: Chunk, q, k, v, v_idx, v_cnt, s_idx, s_cnt, want_lse=False, out=None, ws=None, dca=None):
+    """vs_sparse_attn_prefill, or vs_sparse_attn_prefill_dca when dca = (q_succ, q_inter, chunk, window)
+    is given (q is then the intra-chunk rotation).  Returns out bf16 [C][Hq][D] and lse fp32 [Hq][C] (or None)."""
     for t, nm in ((q, "q"), (k, "k"), (v, "v")):
         _chk_inner(t, nm, ck.head_dim)
     assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k and v.shape[0] >= ck.n_k
@@ -287,14 +303,21 @@ def sparse_attn_prefill(ck: Chunk, q, k, v, v_idx, v_cnt, s_idx, s_cnt, want_lse
     if ws is None:
         ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
     p = ck.params(q=q, k=k, v=v, out=out)
+    if dca is not None:
+        d = _dca_struct(ck, q, dca)
+        _check(lib().vs_sparse_attn_prefill_dca(C.byref(p), _ptr(q), C.byref(d), _ptr(k), _ptr(v), _ptr(v_idx),
+                                                _ptr(v_cnt), _ptr(s_idx), _ptr(s_cnt), _ptr(out), _ptr(lse),
+                                                _ptr(ws), ws.numel(), _stream()), "vs_sparse_attn_prefill_dca")
+        return out, lse
     _check(lib().vs_sparse_attn_prefill(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(v_idx), _ptr(v_cnt),
                                         _ptr(s_idx), _ptr(s_cnt), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
                                         _stream()), "vs_sparse_attn_prefill")
     return out, lse
 
 
-def dense_causal_prefill(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None):
-    """vs_dense_causal_prefill.  Returns out bf16 [C][Hq][D] and lse fp32 [Hq][C] (or None)."""
+def dense_causal_prefill(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None, dca=None):
+    """vs_dense_causal_prefill, or vs_dense_causal_prefill_dca when dca = (q_succ, q_inter, chunk, window)
+    is given.  Returns out bf16 [C][Hq][D] and lse fp32 [Hq][C] (or None)."""
     for t, nm in ((q, "q"), (k, "k"), (v, "v")):
         _chk_inner(t, nm, ck.head_dim)
     assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k and v.shape[0] >= ck.n_k
@@ -306,6 +329,12 @@ def dense_causal_prefill(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None):
     if ws is None:
         ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
     p = ck.params(q=q, k=k, v=v, out=out)
+    if dca is not None:
+        d = _dca_struct(ck, q, dca)
+        _check(lib().vs_dense_causal_prefill_dca(C.byref(p), _ptr(q), C.byref(d), _ptr(k), _ptr(v), _ptr(out),
+                                                 _ptr(lse), _ptr(ws), ws.numel(), _stream()),
+               "vs_dense_causal_prefill_dca")
+        return out, lse
     _check(lib().vs_dense_causal_prefill(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(ws),
                                          ws.numel(), _stream()), "vs_dense_causal_prefill")
     return out, lse

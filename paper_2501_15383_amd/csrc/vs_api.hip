@@ -228,12 +228,27 @@ int vs_refine_step(const vs_params* p, const float* recall, float threshold, int
                                   (hipStream_t)stream));
 }
 
-int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, const void* v,
-                           const int32_t* v_idx, const int32_t* v_cnt, const int32_t* s_idx,
-                           const int32_t* s_cnt, void* out, float* lse, void* ws, size_t ws_bytes,
-                           void* stream) {
+namespace {
+// dca == null: plain attention.  Otherwise the descriptor is checked and turned into DcaArgs.
+int check_dca(const vs_dca* dca, DcaArgs* out) {
+  if (!dca->q_succ || !dca->q_inter || !aligned(dca->q_succ, 16) || !aligned(dca->q_inter, 16))
+    return VS_ERR_INVALID_ARG;
+  if (dca->chunk < 1 || dca->window < 0) return VS_ERR_INVALID_ARG;
+  if (dca->chunk % kBlock != 0 || dca->window % kBlock != 0) return VS_ERR_UNSUPPORTED;
+  if (dca->chunk / kBlock > INT32_MAX || dca->window / kBlock > INT32_MAX) return VS_ERR_INVALID_ARG;
+  out->q_succ = dca->q_succ; out->q_inter = dca->q_inter;
+  out->chunk = dca->chunk; out->window = dca->window;
+  return VS_OK;
+}
+
+int sparse_attn(const vs_params* p, const void* q, const vs_dca* dca, const void* k, const void* v,
+                const int32_t* v_idx, const int32_t* v_cnt, const int32_t* s_idx,
+                const int32_t* s_cnt, void* out, float* lse, void* ws, size_t ws_bytes,
+                void* stream) {
   int rc = check_params(p, true);
   if (rc != VS_OK) return rc;
+  DcaArgs da;
+  if (dca && (rc = check_dca(dca, &da)) != VS_OK) return rc;
   if (!q || !k || !v || !out || !v_idx || !v_cnt || !s_idx || !s_cnt) return VS_ERR_INVALID_ARG;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
@@ -242,14 +257,16 @@ int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, con
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_build_blocklist(*p, s_idx, s_cnt, false, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, k, v, v_idx, v_cnt, false, bl, out, lse,
+  return hip_status(launch_attention(*p, q, dca ? &da : nullptr, k, v, v_idx, v_cnt, false, bl, out, lse,
                                      (char*)ws + blocklist_bytes(*p, false), st));
 }
 
-int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, const void* v,
-                            void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+int dense_attn(const vs_params* p, const void* q, const vs_dca* dca, const void* k, const void* v,
+               void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_params(p, false);
   if (rc != VS_OK) return rc;
+  DcaArgs da;
+  if (dca && (rc = check_dca(dca, &da)) != VS_OK) return rc;
   if (!q || !k || !v || !out) return VS_ERR_INVALID_ARG;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, true));
@@ -258,8 +275,36 @@ int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, co
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_build_blocklist(*p, nullptr, nullptr, true, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, k, v, nullptr, nullptr, true, bl, out, lse,
+  return hip_status(launch_attention(*p, q, dca ? &da : nullptr, k, v, nullptr, nullptr, true, bl, out, lse,
                                      (char*)ws + blocklist_bytes(*p, true), st));
+}
+}  // namespace
+
+int vs_sparse_attn_prefill(const vs_params* p, const void* q, const void* k, const void* v,
+                           const int32_t* v_idx, const int32_t* v_cnt, const int32_t* s_idx,
+                           const int32_t* s_cnt, void* out, float* lse, void* ws, size_t ws_bytes,
+                           void* stream) {
+  return sparse_attn(p, q, nullptr, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse, ws, ws_bytes, stream);
+}
+
+int vs_dense_causal_prefill(const vs_params* p, const void* q, const void* k, const void* v,
+                            void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  return dense_attn(p, q, nullptr, k, v, out, lse, ws, ws_bytes, stream);
+}
+
+int vs_sparse_attn_prefill_dca(const vs_params* p, const void* q_intra, const vs_dca* dca, const void* k,
+                               const void* v, const int32_t* v_idx, const int32_t* v_cnt,
+                               const int32_t* s_idx, const int32_t* s_cnt, void* out, float* lse,
+                               void* ws, size_t ws_bytes, void* stream) {
+  if (!dca) return VS_ERR_INVALID_ARG;
+  return sparse_attn(p, q_intra, dca, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse, ws, ws_bytes, stream);
+}
+
+int vs_dense_causal_prefill_dca(const vs_params* p, const void* q_intra, const vs_dca* dca, const void* k,
+                                const void* v, void* out, float* lse, void* ws, size_t ws_bytes,
+                                void* stream) {
+  if (!dca) return VS_ERR_INVALID_ARG;
+  return dense_attn(p, q_intra, dca, k, v, out, lse, ws, ws_bytes, stream);
 }
 
 int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const void* v, void* out,

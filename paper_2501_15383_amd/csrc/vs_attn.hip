@@ -35,6 +35,12 @@ namespace vs {
 
 struct AttnArgs {
   const __bf16* q;
+  // Dual Chunk Attention (template parameter DCA): the chunk's queries rotated for the
+  // successive-chunk and the inter-chunk pattern (q is the intra-chunk one; same strides),
+  // chunk length and local window in 64-key blocks
+  const __bf16* q_succ;
+  const __bf16* q_inter;
+  int32_t dca_cblk, dca_wblk;
   const __bf16* k;
   const __bf16* v;
   __bf16* out;
@@ -104,7 +110,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int D, int NQB>
+template <int D, int NQB, bool DCA>
 __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   constexpr int DCH = D / 8;           // 16-byte chunks per row
   constexpr int DSTEPS = D / 16;       // MFMA k-steps of QK^T
@@ -126,6 +132,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   __bf16* const Vs = Ks + 2 * TILE;                   // [2][TILE]
   int32_t* const vidx_s = (int32_t*)(Vs + 2 * TILE);  // [2][64]
   uint8_t* const need_s = (uint8_t*)(vidx_s + 2 * 64);  // [waves][64], private to each wave
+  static_assert(2 * (2 * NQB) * 64 <= 8 * 64, "need_s and dcak_s share the 8 x 64 bytes");
+  uint8_t* const dcak_s = need_s + 2 * NQB * 64;        // [waves][64], DCA pattern code of a tile's keys
   const uint32_t ks_addr = lds_address(Ks), vs_addr = lds_address(Vs);
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -203,13 +211,24 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const __bf16* vbase = a.v + (int64_t)g * a.v_stride_head;
 
   // ---- Q^T operand: lane (i = lane%32, hh) holds Q[i][16 st + 8 hh .. +7] ----------------
+  // With DCA the operand is one of three rotations of the same rows; q_var says which one the
+  // registers hold (the walk goes from the query block's own keys backwards, so it changes
+  // at most a few times per tile).
   bf16x8 qreg[DSTEPS];
-  {
+  int q_var = 0;
+  auto load_q = [&](int var) {
+    const __bf16* qb = a.q;
+    if constexpr (DCA) {
+      if (var == 1) qb = a.q_succ;
+      if (var == 2) qb = a.q_inter;
+    }
     const int64_t rc = row < a.q_len ? row : a.q_len - 1;
-    const __bf16* qp = a.q + rc * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
+    const __bf16* qp = qb + rc * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
 #pragma unroll
     for (int st = 0; st < DSTEPS; ++st) qreg[st] = *(const bf16x8*)(qp + 16 * st);
-  }
+    q_var = var;
+  };
+  load_q(0);
 
   f32x16 oacc[DB];
 #pragma unroll
@@ -439,14 +458,49 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // K Q^T of a masked tile, of the first tile of a row block, or of a tile whose scores
   // outran the reference: true maximum first, then the exponentials.  Nothing may be pending
   // (the accumulators must be up to date when the reference moves).  Leaves the tile pending.
+  int need_var = 0;       // DCA: rotation this wave's tile needs; 3 = it differs inside the tile (codes in dcak_s)
+  uint32_t dca_need = 0;  //      need_var == 3: bit v set iff some usable element needs rotation v
+  bool qsw = false;       //      the registers hold another rotation than the tile needs
   auto qk_exact = [&](const __bf16* kb, bool diag, bool vert, auto&& apply_mask) {
     f32x16 s0, s1;
 #pragma unroll
     for (int x = 0; x < 16; ++x) { s0[x] = 0.f; s1[x] = 0.f; }
+    if (DCA && need_var == 3) {
+      // one product per rotation that occurs in the tile; an element takes the product of its
+      // own pattern.  Code of key r: 100 = intra-chunk; otherwise a threshold thr: rows
+      // il < thr are inside the local window (successive-chunk), the others inter-chunk.
 #pragma unroll
-    for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
+      for (int var = 0; var < 3; ++var) {
+        if (!((dca_need >> var) & 1u)) continue;
+        if (q_var != var) load_q(var);
 #pragma unroll
-    for (int st = 0; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
+        for (int jb = 0; jb < 2; ++jb) {
+          f32x16 tt;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) tt[x] = 0.f;
+#pragma unroll
+          for (int st = 0; st < DSTEPS; ++st) qk_step(tt, kb, jb, st);
+#pragma unroll
+          for (int xq = 0; xq < 4; ++xq) {
+            const uint32_t cd = *(const uint32_t*)&dcak_s[wv * 64 + 32 * jb + 8 * xq + 4 * hh];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              const int code = (int)((cd >> (8 * x)) & 255u);
+              const int ev = code == 100 ? 0 : (il < code ? 1 : 2);
+              if (ev == var) {
+                if (jb == 0) s0[4 * xq + x] = tt[4 * xq + x];
+                else s1[4 * xq + x] = tt[4 * xq + x];
+              }
+            }
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int st = 0; st < DSTEPS; ++st) qk_step(s0, kb, 0, st);
+#pragma unroll
+      for (int st = 0; st < DSTEPS; ++st) qk_step(s1, kb, 1, st);
+    }
     if (diag || vert) {
       apply_mask(s0, 0);
       apply_mask(s1, 1);
@@ -622,6 +676,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     vbp = Vs + (buf ^ 1) * TILE;
     part = wave_valid && !last;
     diag = false;
+    bool usable = false;  // vertical tile: this lane's key can be used by some row of the block
     if (__builtin_expect(cur_kind == 0, 1)) {
       part = part && ((cur_mask >> t) & 1);
       diag = cur_idx - (NQB - 1) + t == 0;  // block diagonal 0 of (query block t, this key block)
@@ -632,9 +687,46 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       int need = 64;
       if (pos < vcnt && ad >= 0 && !bm_test(bmA, ad)) need = ad == 0 ? (j & 63) : 0;
       need_s[wv * 64 + lane] = (uint8_t)need;
-      part = part && __ballot(need < 64) != 0;
+      usable = need < 64;
+      part = part && __ballot(usable) != 0;
     }
     vert = cur_kind == 1;
+    if constexpr (DCA) {
+      // which rotation of Q meets this tile's keys (section 5.1, DCA paragraph): keys of the
+      // query block's own chunk the intra-chunk one; keys of the chunk before it, closer than
+      // the local window, the successive-chunk one; all others the inter-chunk one
+      qsw = false;
+      if (part) {
+        const int m = m0 + t, cq = m / a.dca_cblk;
+        if (cur_kind == 0) {
+          const int dblk = cur_idx - (NQB - 1) + t;  // block distance, >= 0 for a tile this wave takes
+          const int ck = (m - dblk) / a.dca_cblk;
+          if (ck == cq) need_var = 0;
+          else if (ck == cq - 1 && dblk < a.dca_wblk) need_var = 1;
+          else if (ck == cq - 1 && dblk == a.dca_wblk) {
+            // the window ends inside this block: distance 64 dblk + il - r < window iff il < r
+            need_var = 3;
+            dca_need = 6u;
+            dcak_s[wv * 64 + lane] = (uint8_t)lane;
+          } else need_var = 2;
+        } else {
+          const int j = vidx_s[buf * 64 + lane];
+          const int ck = (j >> 6) / a.dca_cblk;
+          int code = 0;
+          if (ck == cq) code = 100;
+          else if (ck == cq - 1) {
+            const int64_t thr = 64 * (int64_t)a.dca_wblk - (64 * (int64_t)m - j);  // il < thr: inside the window
+            code = thr < 0 ? 0 : (thr > 64 ? 64 : (int)thr);
+          }
+          dcak_s[wv * 64 + lane] = (uint8_t)code;
+          dca_need = (__ballot(usable && code == 100) != 0 ? 1u : 0u) |
+                     (__ballot(usable && code != 100 && code > 0) != 0 ? 2u : 0u) |
+                     (__ballot(usable && code < 64) != 0 ? 4u : 0u);
+          need_var = 3;
+        }
+        qsw = need_var != q_var;
+      }
+    }
   };
   // copies of K(i + 1) and V(i) into the buffers that step i - 1 used last
   auto launch_copies = [&]() {
@@ -656,7 +748,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   for (;;) {
     classify();
     // steady state: runs of steps in which this wave multiplies tile i and folds in tile i - 1
-    while (__builtin_expect(pend && part && !(diag || vert || !have_max), 1)) {
+    while (__builtin_expect(pend && part && !(diag || vert || !have_max) && !(DCA && qsw), 1)) {
       if (__builtin_expect(!fused(kb, vbp, launch_copies), 0)) qk_exact(kb, diag, vert, apply_mask);
       end_step();
       classify();
@@ -664,6 +756,12 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     launch_copies();
     if (pend) drain(vbp);
     bool exact = diag || vert || !have_max;
+    if constexpr (DCA) {
+      if (part && qsw) {
+        if (need_var < 3) load_q(need_var);
+        else exact = true;
+      }
+    }
     if (part && !exact) exact = !qk_fast(kb);
     if (__builtin_expect(part && exact, 0)) qk_exact(kb, diag, vert, apply_mask);
     if (last) break;
@@ -839,13 +937,17 @@ __global__ __launch_bounds__(256) void k_fill_zero_u32(uint32_t* p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
-hipError_t launch_attention(const vs_params& p, const void* q, const void* k, const void* v,
+hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
                             const BlockList& bl, void* out, float* lse, void* sync_ws, hipStream_t st) {
   constexpr int NQB = kAttnQBlocks;
   if (!sync_ws) return hipErrorInvalidValue;
   AttnArgs a;
   a.q = (const __bf16*)q; a.k = (const __bf16*)k; a.v = (const __bf16*)v;
+  a.q_succ = dca ? (const __bf16*)dca->q_succ : nullptr;
+  a.q_inter = dca ? (const __bf16*)dca->q_inter : nullptr;
+  a.dca_cblk = dca ? (int32_t)(dca->chunk / kBlock) : 0;
+  a.dca_wblk = dca ? (int32_t)(dca->window / kBlock) : 0;
   a.out = (__bf16*)out; a.lse = lse;
   a.q_stride_tok = p.q_stride_tok; a.q_stride_head = p.q_stride_head;
   a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
@@ -886,18 +988,25 @@ hipError_t launch_attention(const vs_params& p, const void* q, const void* k, co
   // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention<128, NQB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes<128>());
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attention<64, NQB>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, attn_lds_bytes<64>());
-    if (e != hipSuccess) return e;
+    const void* fns[4] = {reinterpret_cast<const void*>(&k_attention<128, NQB, false>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, false>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, true>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, true>)};
+    for (int i = 0; i < 4; ++i) {
+      const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               i % 2 == 0 ? attn_lds_bytes<128>() : attn_lds_bytes<64>());
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
-  if (p.head_dim == 128)
-    hipLaunchKernelGGL((k_attention<128, NQB>), dim3((unsigned)a.n_wg), dim3(128 * NQB), attn_lds_bytes<128>(), st, a);
-  else
-    hipLaunchKernelGGL((k_attention<64, NQB>), dim3((unsigned)a.n_wg), dim3(128 * NQB), attn_lds_bytes<64>(), st, a);
+  const dim3 grid((unsigned)a.n_wg), block(128 * NQB);
+  if (p.head_dim == 128) {
+    if (dca) hipLaunchKernelGGL((k_attention<128, NQB, true>), grid, block, attn_lds_bytes<128>(), st, a);
+    else hipLaunchKernelGGL((k_attention<128, NQB, false>), grid, block, attn_lds_bytes<128>(), st, a);
+  } else {
+    if (dca) hipLaunchKernelGGL((k_attention<64, NQB, true>), grid, block, attn_lds_bytes<64>(), st, a);
+    else hipLaunchKernelGGL((k_attention<64, NQB, false>), grid, block, attn_lds_bytes<64>(), st, a);
+  }
   return hipGetLastError();
 }
 

@@ -61,8 +61,15 @@ static inline BlockList blocklist_layout(const vs_params& p, bool dense, void* w
 // ---- launchers (defined in the .hip files; all enqueue on `st`, return hipError_t) ------
 hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, const int32_t* s_cnt,
                                   bool dense, const BlockList& bl, hipStream_t st);
-// sync_ws: attn_sync_bytes(p) bytes of counters (zero-filled by the launch itself)
-hipError_t launch_attention(const vs_params& p, const void* q, const void* k, const void* v,
+// Dual Chunk Attention: the two other rotations of the chunk's queries (same strides as q),
+// chunk length and local window in tokens (multiples of 64)
+struct DcaArgs {
+  const void* q_succ;
+  const void* q_inter;
+  int64_t chunk, window;
+};
+// sync_ws: attn_sync_bytes(p) bytes of counters (zero-filled by the launch itself); dca may be null
+hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
                             const BlockList& bl, void* out, float* lse, void* sync_ws, hipStream_t st);
 size_t attn_sync_bytes(const vs_params& p);

@@ -1,0 +1,83 @@
+"""GPU parity of the Dual Chunk Attention variants (section 5.1; "Integrating with DCA",
+section 5.2) against the fp64 oracle, element by element, through the C ABI.  The three
+rotations of the queries are independent random tensors here, which makes every wrong choice
+of pattern visible."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2501_15383_amd as vs
+from gpu_util import assert_attn_close, chunk_of, dev
+from helpers import rand_bf16
+from test_gpu_attention import _rand_sets, _t
+
+pytestmark = pytest.mark.gpu
+
+
+def _inputs(rng, hq, hkv, d, c, s):
+    qs = [rand_bf16(rng, (c, hq, d)) for _ in range(3)]
+    k = rand_bf16(rng, (s + c, hkv, d)); v = rand_bf16(rng, (s + c, hkv, d))
+    return qs, k, v
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,s,chunk,window", [
+    (4, 1, 64, 256, 512, 256, 128),     # chunk boundary at the start of the query chunk
+    (4, 2, 128, 320, 448, 192, 64),     # boundaries inside the query chunk and inside query tiles
+    (2, 1, 128, 200, 1280, 512, 256),   # ragged chunk, two chunks back = inter
+    (7, 1, 128, 130, 640, 64, 64),      # smallest chunk: every block its own chunk
+    (2, 2, 64, 256, 256, 128, 0),       # no local window
+    (2, 1, 128, 192, 320, 128, 384),    # window longer than the chunk
+    (3, 1, 64, 128, 384, 4096, 64),     # one chunk holds everything: intra only
+])
+def test_dense_dca_matches_oracle(hq, hkv, d, c, s, chunk, window):
+    rng = np.random.default_rng(700 + c + chunk)
+    qs, k, v = _inputs(rng, hq, hkv, d, c, s)
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d))
+    ref_out, ref_lse = oracle.dense_attention(pb, qs[0], k, v, dca=oracle.Dca(chunk, window, qs[1], qs[2]))
+    out, lse = vs.dense_causal_prefill(chunk_of(pb), dev(qs[0]), dev(k), dev(v), want_lse=True,
+                                       dca=(dev(qs[1]), dev(qs[2]), chunk, window))
+    torch.cuda.synchronize()
+    assert_attn_close(out, lse, ref_out, ref_lse, f"dense dca C={c} s={s} chunk={chunk} window={window}")
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,s,nv,ns,band,chunk,window", [
+    (4, 1, 64, 512, 1024, 60, 12, 64, 512, 128),
+    (4, 2, 128, 320, 960, 150, 20, 64, 256, 64),    # vertical columns of all three patterns in one tile
+    (2, 1, 128, 256, 512, 70, 6, 0, 128, 128),
+    (7, 1, 128, 200, 1280, 130, 30, 64, 640, 192),
+])
+def test_sparse_dca_matches_oracle_on_given_sets(hq, hkv, d, c, s, nv, ns, band, chunk, window):
+    rng = np.random.default_rng(800 + c)
+    qs, k, v = _inputs(rng, hq, hkv, d, c, s)
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d), vertical_budget=nv + 8, slash_budget=ns + band + 8,
+                        keep_first_cols=1 if band else 0, keep_local_band=band)
+    sets = _rand_sets(rng, pb, nv, ns, force_cols=[0] if band else [], force_offs=range(band))
+    ref_out, ref_lse = oracle.sparse_attention(pb, qs[0], k, v, *sets, dca=oracle.Dca(chunk, window, qs[1], qs[2]))
+    out, lse = vs.sparse_attn_prefill(chunk_of(pb), dev(qs[0]), dev(k), dev(v), *[_t(x) for x in sets],
+                                      want_lse=True, dca=(dev(qs[1]), dev(qs[2]), chunk, window))
+    torch.cuda.synchronize()
+    assert_attn_close(out, lse, ref_out, ref_lse, f"sparse dca C={c} s={s} chunk={chunk} window={window}")
+
+
+def test_dca_with_equal_rotations_is_the_plain_kernel():
+    rng = np.random.default_rng(900)
+    hq, hkv, d, c, s = 4, 1, 128, 256, 768
+    qs, k, v = _inputs(rng, hq, hkv, d, c, s)
+    ck = chunk_of(oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d)))
+    q = dev(qs[0])
+    plain, lse_p = vs.dense_causal_prefill(ck, q, dev(k), dev(v), want_lse=True)
+    same, lse_s = vs.dense_causal_prefill(ck, q, dev(k), dev(v), want_lse=True, dca=(q.clone(), q.clone(), 256, 128))
+    torch.cuda.synchronize()
+    assert (plain.float() - same.float()).abs().max().item() <= 2e-2
+    assert (lse_p - lse_s).abs().max().item() < 1e-3
+
+
+def test_dca_argument_checks():
+    ck = vs.Chunk(2, 1, 64, 64, 0, 0.125)
+    q = torch.zeros((64, 2, 64), dtype=torch.bfloat16, device="cuda"); kv = torch.zeros((64, 1, 64), dtype=torch.bfloat16, device="cuda")
+    for chunk, window, status in ((100, 64, vs.VS_ERR_UNSUPPORTED), (128, 10, vs.VS_ERR_UNSUPPORTED),
+                                  (0, 64, vs.VS_ERR_INVALID_ARG), (128, -64, vs.VS_ERR_INVALID_ARG)):
+        with pytest.raises(vs.VsError) as e:
+            vs.dense_causal_prefill(ck, q, kv, kv, dca=(q, q, chunk, window))
+        assert e.value.status == status
