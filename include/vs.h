@@ -207,6 +207,9 @@ int vs_sparse_attn_prefill_dca(const vs_params *p, const void *q_intra, const vs
 int vs_dense_causal_prefill_dca(const vs_params *p, const void *q_intra, const vs_dca *dca,
                                 const void *k, const void *v, void *out, float *lse, void *ws,
                                 size_t ws_bytes, void *stream);
+int vs_estimate_dca(const vs_params *p, const void *q_intra, const vs_dca *dca, const void *k,
+                    float *vscore, float *sscore, float *lse_lastq, void *ws, size_t ws_bytes,
+                    void *stream);
 
 /* Cost model and chunk planner (host functions; sec. 6.3 "Dynamic Chunked Pipeline
  * Parallelism": chunk sizes are adjusted to the complexity of the attention

@@ -97,7 +97,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
            "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step",
-           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca"]
+           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca", "vs_estimate_dca"]
 
 
 def status_string(status: int) -> str:
@@ -188,8 +188,9 @@ def _chk_inner(t, name, d):
     assert t.dtype == torch.bfloat16 and t.dim() == 3 and t.stride(2) == 1 and t.shape[2] == d, name
 
 
-def estimate(ck: Chunk, q, k, want_lse=False, vscore=None, sscore=None, ws=None):
-    """vs_estimate.  q: bf16 [C][Hq][D] (the chunk), k: bf16 [>=n_k][Hkv][D].
+def estimate(ck: Chunk, q, k, want_lse=False, vscore=None, sscore=None, ws=None, dca=None):
+    """vs_estimate, or vs_estimate_dca when dca = (q_succ, q_inter, chunk, window) is given.
+    q: bf16 [C][Hq][D] (the chunk), k: bf16 [>=n_k][Hkv][D].
     Returns vscore, sscore (fp32 [Hq][n_k]) and lse_lastq (fp32 [Hq][W'] or None).
     vscore / sscore / ws may be passed in to avoid allocating."""
     _chk_inner(q, "q", ck.head_dim); _chk_inner(k, "k", ck.head_dim)
@@ -205,6 +206,11 @@ def estimate(ck: Chunk, q, k, want_lse=False, vscore=None, sscore=None, ws=None)
     if ws is None:
         ws = torch.empty(max(workspace_bytes(ck, VS_WS_ESTIMATE), 256), dtype=torch.uint8, device=dev)
     p = ck.params(q=q, k=k)
+    if dca is not None:
+        d = _dca_struct(ck, q, dca)
+        _check(lib().vs_estimate_dca(C.byref(p), _ptr(q), C.byref(d), _ptr(k), _ptr(vscore), _ptr(sscore), _ptr(lse),
+                                     _ptr(ws), ws.numel(), _stream()), "vs_estimate_dca")
+        return vscore, sscore, lse
     _check(lib().vs_estimate(C.byref(p), _ptr(q), _ptr(k), _ptr(vscore), _ptr(sscore), _ptr(lse),
                              _ptr(ws), ws.numel(), _stream()), "vs_estimate")
     return vscore, sscore, lse

@@ -172,15 +172,34 @@ float vs_yarn_softmax_scale(float s, int32_t head_dim) {
   return r * r / sqrtf((float)head_dim);
 }
 
-int vs_estimate(const vs_params* p, const void* q, const void* k, float* vscore, float* sscore,
-                float* lse_lastq, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+int check_dca(const vs_dca* dca, DcaArgs* out);
+
+int estimate_any(const vs_params* p, const void* q, const vs_dca* dca, const void* k, float* vscore,
+                 float* sscore, float* lse_lastq, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_params(p, false);
   if (rc != VS_OK) return rc;
+  DcaArgs da;
+  if (dca && (rc = check_dca(dca, &da)) != VS_OK) return rc;
   if (!q || !k || !vscore || !sscore) return VS_ERR_INVALID_ARG;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(vscore, 4) || !aligned(sscore, 4)) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, estimate_ws_bytes(*p));
   if (rc != VS_OK) return rc;
-  return hip_status(launch_estimate(*p, q, k, vscore, sscore, lse_lastq, ws, (hipStream_t)stream));
+  return hip_status(launch_estimate(*p, q, dca ? &da : nullptr, k, vscore, sscore, lse_lastq, ws,
+                                    (hipStream_t)stream));
+}
+}  // namespace
+
+int vs_estimate(const vs_params* p, const void* q, const void* k, float* vscore, float* sscore,
+                float* lse_lastq, void* ws, size_t ws_bytes, void* stream) {
+  return estimate_any(p, q, nullptr, k, vscore, sscore, lse_lastq, ws, ws_bytes, stream);
+}
+
+int vs_estimate_dca(const vs_params* p, const void* q_intra, const vs_dca* dca, const void* k,
+                    float* vscore, float* sscore, float* lse_lastq, void* ws, size_t ws_bytes,
+                    void* stream) {
+  if (!dca) return VS_ERR_INVALID_ARG;
+  return estimate_any(p, q_intra, dca, k, vscore, sscore, lse_lastq, ws, ws_bytes, stream);
 }
 
 int vs_select(const vs_params* p, const float* vscore, const float* sscore, int32_t* v_idx,

@@ -78,7 +78,7 @@ hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const in
                               const BlockList& bl, int64_t* tiles, hipStream_t st);
 
 size_t estimate_ws_bytes(const vs_params& p);
-hipError_t launch_estimate(const vs_params& p, const void* q, const void* k, float* vscore,
+hipError_t launch_estimate(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, float* vscore,
                            float* sscore, float* lse_lastq, void* ws, hipStream_t st);
 
 size_t select_ws_bytes(const vs_params& p);

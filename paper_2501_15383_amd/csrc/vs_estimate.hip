@@ -26,6 +26,12 @@ constexpr int kEstRange = 1024;  // keys per workgroup
 
 struct EstArgs {
   const __bf16* q;
+  // Dual Chunk Attention (template parameter DCA; section 5.1 and "Integrating with DCA" in
+  // section 5.2): the window rows rotated for the successive-chunk and the inter-chunk pattern
+  // (q is the intra-chunk one; same strides), chunk length and local window in tokens
+  const __bf16* q_succ;
+  const __bf16* q_inter;
+  int64_t dca_chunk, dca_window;
   const __bf16* k;
   int64_t q_stride_tok, q_stride_head, k_stride_tok, k_stride_head;
   float* vscore;
@@ -40,7 +46,7 @@ struct EstArgs {
   float scale_log2;
 };
 
-template <int D, int NH, int PASS>
+template <int D, int NH, int PASS, bool DCA>
 __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
   constexpr int NW = 2 * NH, NT = 64 * NW, KS = D + 8, DCH = D / 8, DSTEPS = D / 16;
   constexpr int KPT = (64 * DCH + NT - 1) / NT;
@@ -62,15 +68,37 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
   const int n_tiles = (int)((jb_ - ja + 63) >> 6);
   const __bf16* kbase = a.k + (int64_t)g * a.k_stride_head;
 
-  // window rows of this wave, as MFMA operand: lane (r = 32 ib + lane%32, hh)
+  // window rows of this wave, as MFMA operand: lane (r = 32 ib + lane%32, hh).  With DCA the
+  // operand is one of three rotations of the same rows; q_var says which one is loaded.
   bf16x8 qreg[DSTEPS];
-  {
+  int q_var = 0;
+  auto load_q = [&](int var) {
+    const __bf16* qb = a.q;
+    if constexpr (DCA) {
+      if (var == 1) qb = a.q_succ;
+      if (var == 2) qb = a.q_inter;
+    }
     int r = 32 * ib + (lane & 31);
     if (r > a.wp - 1) r = a.wp - 1;
-    const __bf16* qp = a.q + (a.q_len - a.wp + r) * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
+    const __bf16* qp = qb + (a.q_len - a.wp + r) * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
 #pragma unroll
     for (int st = 0; st < DSTEPS; ++st) qreg[st] = *(const bf16x8*)(qp + 16 * st);
-  }
+    q_var = var;
+  };
+  load_q(0);
+  // DCA: chunk of the wave's first row, and the position at which its rows enter the next chunk
+  const int64_t dca_c = DCA ? a.dca_chunk : 1;
+  const int64_t pos_lo = a.p0 + 32 * ib, pos_hi = pos_lo + 31;
+  const int64_t cq_lo = DCA ? pos_lo / dca_c : 0, cq_hi = DCA ? pos_hi / dca_c : 0;
+  const int64_t dca_bound = (cq_lo + 1) * dca_c;
+  // pattern of (window row r of this wave's half, key j) for a tile whose keys lie in chunk ck
+  auto var_of = [&](int64_t ck, int r_in_half, int64_t j) -> int {
+    const int64_t pos = pos_lo + r_in_half;
+    const int64_t cq = cq_lo + (pos >= dca_bound ? 1 : 0);
+    if (ck == cq) return 0;
+    if (ck == cq - 1 && pos - j < a.dca_window) return 1;
+    return 2;
+  };
 
   float* const my_strip = &strip[PASS == 1 ? wv * STRIP : 0];
   if (PASS == 1) {
@@ -125,6 +153,28 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
     const int64_t j0 = ja + 64 * tile;
     const bool need_mask = j0 + 63 > a.p0;  // some (row, key) of this tile is acausal
 
+    // DCA: which rotation(s) this wave's rows need against the keys of this tile (all in chunk ck)
+    uint32_t need = 1u;
+    int64_t ck = 0;
+    if constexpr (DCA) {
+      ck = j0 / dca_c;
+      if (cq_lo == cq_hi) {
+        if (ck == cq_lo) need = 1u;
+        else if (ck == cq_lo - 1) {
+          if (pos_hi - j0 < a.dca_window) need = 2u;              // the largest distance is inside the window
+          else if (pos_lo - (j0 + 63) >= a.dca_window) need = 4u;  // the smallest one is outside
+          else need = 6u;
+        } else need = 4u;
+      } else {
+        need = ck < cq_lo - 1 ? 4u : 7u;  // rows on both sides of a chunk boundary
+      }
+      if (head_ok && (need & (need - 1)) == 0) {  // one rotation for the whole tile
+        const int var = need == 1u ? 0 : (need == 2u ? 1 : 2);
+        if (q_var != var) load_q(var);
+      }
+    }
+    const bool multi = DCA && (need & (need - 1)) != 0;
+
     if (head_ok) {
       if (PASS == 1 && ib == 0 && tile > 0) flush_columns(tile - 1);
       float col[2];
@@ -136,9 +186,28 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
         for (int x = 0; x < 16; ++x) s[x] = 0.f;
         if (PASS == 0) {
           // D[j][i]: lane = query i, element x = key 32 jb + 8 (x/4) + 4 hh + (x%4)
+          if (multi) {
+            // one product per rotation; element x (key 32 jb + 8 (x/4) + 4 hh + (x%4)) of lane
+            // (row lane%32) keeps the product of its own pattern
 #pragma unroll
-          for (int st = 0; st < DSTEPS; ++st)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], s, 0, 0, 0);
+            for (int var = 0; var < 3; ++var) {
+              if (!((need >> var) & 1u)) continue;
+              if (q_var != var) load_q(var);
+              f32x16 tt;
+#pragma unroll
+              for (int x = 0; x < 16; ++x) tt[x] = 0.f;
+#pragma unroll
+              for (int st = 0; st < DSTEPS; ++st)
+                tt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], tt, 0, 0, 0);
+#pragma unroll
+              for (int x = 0; x < 16; ++x)
+                if (var_of(ck, lane & 31, j0 + 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3)) == var) s[x] = tt[x];
+            }
+          } else {
+#pragma unroll
+            for (int st = 0; st < DSTEPS; ++st)
+              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], s, 0, 0, 0);
+          }
           if (need_mask) {
             // key j is masked for query r iff j - p0 > r; dr = r - (j0 - p0) - 32 jb - 4 hh
             const int dr = 32 * ib + (lane & 31) - (int)(j0 - a.p0) - 32 * jb - 4 * hh;
@@ -159,6 +228,23 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
           mrun = m_new;
         } else {
           // D[i][j]: lane = key j = 32 jb + lane%32, element x = query 32 ib + 8 (x/4) + 4 hh + (x%4)
+          if (multi) {
+            // as in sweep A; here a lane is key 32 jb + lane%32 and element x is row 8 (x/4) + 4 hh + (x%4)
+#pragma unroll
+            for (int var = 0; var < 3; ++var) {
+              if (!((need >> var) & 1u)) continue;
+              if (q_var != var) load_q(var);
+              f32x16 tt;
+#pragma unroll
+              for (int x = 0; x < 16; ++x) tt[x] = 0.f;
+#pragma unroll
+              for (int st = 0; st < DSTEPS; ++st)
+                tt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[st], *(const bf16x8*)(kfp + 16 * st), tt, 0, 0, 0);
+#pragma unroll
+              for (int x = 0; x < 16; ++x)
+                if (var_of(ck, 8 * (x >> 2) + 4 * hh + (x & 3), j0 + 32 * jb + (lane & 31)) == var) s[x] = tt[x];
+            }
+          } else
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
             // K operands in two batches, so that only half of them are live at a time
@@ -291,16 +377,26 @@ size_t estimate_ws_bytes(const vs_params& p) {
 template <int D, int NH>
 static hipError_t launch_est(const EstArgs& a, int hb, hipStream_t st) {
   const dim3 grid(a.n_ranges, a.n_kv_heads, hb);
-  hipLaunchKernelGGL((k_estimate<D, NH, 0>), grid, dim3(128 * NH), 0, st, a);
+  if (a.dca_chunk > 0) {
+    hipLaunchKernelGGL((k_estimate<D, NH, 0, true>), grid, dim3(128 * NH), 0, st, a);
+    hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(1024), 0, st, a);
+    hipLaunchKernelGGL((k_estimate<D, NH, 1, true>), grid, dim3(128 * NH), 0, st, a);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL((k_estimate<D, NH, 0, false>), grid, dim3(128 * NH), 0, st, a);
   hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(1024), 0, st, a);
-  hipLaunchKernelGGL((k_estimate<D, NH, 1>), grid, dim3(128 * NH), 0, st, a);
+  hipLaunchKernelGGL((k_estimate<D, NH, 1, false>), grid, dim3(128 * NH), 0, st, a);
   return hipGetLastError();
 }
 
-hipError_t launch_estimate(const vs_params& p, const void* q, const void* k, float* vscore,
+hipError_t launch_estimate(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, float* vscore,
                            float* sscore, float* lse_lastq, void* ws, hipStream_t st) {
   EstArgs a;
   a.q = (const __bf16*)q; a.k = (const __bf16*)k;
+  a.q_succ = dca ? (const __bf16*)dca->q_succ : nullptr;
+  a.q_inter = dca ? (const __bf16*)dca->q_inter : nullptr;
+  a.dca_chunk = dca ? dca->chunk : 0;
+  a.dca_window = dca ? dca->window : 0;
   a.q_stride_tok = p.q_stride_tok; a.q_stride_head = p.q_stride_head;
   a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
   a.vscore = vscore; a.sscore = sscore; a.lse_lastq = lse_lastq;

@@ -81,3 +81,28 @@ def test_dca_argument_checks():
         with pytest.raises(vs.VsError) as e:
             vs.dense_causal_prefill(ck, q, kv, kv, dca=(q, q, chunk, window))
         assert e.value.status == status
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,s,w,chunk,window", [
+    (4, 1, 64, 1024, 3072, 64, 1024, 256),    # window rows at the end of a chunk; window boundary inside a key tile row
+    (7, 1, 128, 300, 2048, 64, 512, 128),     # ragged n_k: the window rows straddle 64-blocks
+    (4, 2, 128, 96, 1984, 64, 2048, 64),      # ... and a chunk boundary (rows 2048.. enter the next chunk)
+    (5, 1, 128, 40, 0, 64, 64, 64),           # chunk shorter than the window, first chunk
+    (8, 2, 128, 128, 1152, 16, 128, 0),       # short window of rows, no local window
+    (2, 1, 64, 256, 1792, 64, 64, 192),       # smallest chunk
+    (3, 3, 64, 128, 384, 64, 4096, 64),       # intra only
+])
+def test_estimate_dca_matches_oracle(hq, hkv, d, c, s, w, chunk, window):
+    from gpu_util import f64
+    rng = np.random.default_rng(1000 + c + chunk)
+    n_k = s + c
+    qs = [rand_bf16(rng, (c, hq, d)) for _ in range(3)]
+    k = rand_bf16(rng, (n_k, hkv, d))
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d), last_q=w)
+    rvs, rss, rlse = oracle.estimate(pb, qs[0], k, dca=oracle.Dca(chunk, window, qs[1], qs[2]))
+    vsc, ssc, lse = vs.estimate(chunk_of(pb), dev(qs[0]), dev(k), want_lse=True,
+                                dca=(dev(qs[1]), dev(qs[2]), chunk, window))
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(f64(lse), rlse, atol=2e-4, rtol=0)
+    np.testing.assert_allclose(f64(vsc), rvs, rtol=2e-4, atol=1e-7)
+    np.testing.assert_allclose(f64(ssc), rss, rtol=2e-4, atol=1e-7)
