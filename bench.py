@@ -31,7 +31,7 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def cpu_baseline(w, pb_kwargs, Q, K, V, sets_host, target_s):
+def cpu_baseline(w, pb_kwargs, Q, K, V, sets_host, target_s, dca=None):
     """Time the fp64 oracle on a bounded sample of this chunk and extrapolate to the chunk."""
     import numpy as np
 
@@ -40,8 +40,9 @@ def cpu_baseline(w, pb_kwargs, Q, K, V, sets_host, target_s):
     pb = oracle.Problem(**pb_kwargs)
     qh, kh, vh = vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V)
     cores = oracle.num_threads()
+    od = None if dca is None else oracle.Dca(dca[2], dca[3], vsgen.as_u16(dca[0]), vsgen.as_u16(dca[1]))
     t0 = time.time()
-    vs_, ss_, _ = oracle.estimate(pb, qh, kh, heads=[0])
+    vs_, ss_, _ = oracle.estimate(pb, qh, kh, heads=[0], dca=od)
     t_est = time.time() - t0
     t0 = time.time()
     oracle.select_one(vs_[0], pb.vertical_budget, pb.keep_first_cols)
@@ -50,14 +51,14 @@ def cpu_baseline(w, pb_kwargs, Q, K, V, sets_host, target_s):
     # attention rows: spread over the chunk, sized from a 2-row probe to fill the time budget
     rng = np.random.default_rng(7)
     t0 = time.time()
-    oracle.sparse_attention(pb, qh, kh, vh, *sets_host, heads=[0], rows=[0, pb.q_len - 1])
+    oracle.sparse_attention(pb, qh, kh, vh, *sets_host, heads=[0], rows=[0, pb.q_len - 1], dca=od)
     t_probe = max(time.time() - t0, 1e-3)
     budget = max(target_s - t_est - t_sel - t_probe, 1.0)
     # two rows ran side by side, so one row costs about t_probe on one core
     n_rows = int(min(pb.q_len, cores * max(1, int(budget / t_probe))))
     rows = np.sort(rng.choice(pb.q_len, n_rows, replace=False))
     t0 = time.time()
-    oracle.sparse_attention(pb, qh, kh, vh, *sets_host, heads=[0], rows=rows)
+    oracle.sparse_attention(pb, qh, kh, vh, *sets_host, heads=[0], rows=rows, dca=od)
     t_att = time.time() - t0
     hq = pb.n_q_heads
     chunk_s = hq * (t_est + t_sel) + t_att * (hq * pb.q_len) / n_rows
@@ -115,7 +116,12 @@ def main():
 
     t0 = time.time()
     K, V = vsgen.make_kv(w, n_k, device=dev)
-    Q = vsgen.make_q(w, s, s + C, device=dev)
+    dca = None   # Dual Chunk Attention workloads: (q_succ, q_inter, chunk, window) next to the intra-chunk Q
+    if w.dca_chunk > 0:
+        Q, q_succ, q_inter = vsgen.make_q_dca(w, s, s + C, device=dev)
+        dca = (q_succ, q_inter, w.dca_chunk, w.dca_window)
+    else:
+        Q = vsgen.make_q(w, s, s + C, device=dev)
     torch.cuda.synchronize()
     t_gen = time.time() - t0
 
@@ -136,14 +142,14 @@ def main():
         # HIP events between them give the per-kernel times
         if ev: ev[0].record()
         if w.dense:
-            vs.dense_causal_prefill(ck, Q, K, V, out=out, ws=ws_a)
+            vs.dense_causal_prefill(ck, Q, K, V, out=out, ws=ws_a, dca=dca)
             if ev: ev[1].record(); ev[2].record(); ev[3].record()
             return
-        vs.estimate(ck, Q, K, vscore=vscore, sscore=sscore, ws=ws_e)
+        vs.estimate(ck, Q, K, vscore=vscore, sscore=sscore, ws=ws_e, dca=dca)
         if ev: ev[1].record()
         vs.select(ck, vscore, sscore, sets=sets)
         if ev: ev[2].record()
-        vs.sparse_attn_prefill(ck, Q, K, V, *sets, out=out, ws=ws_a)
+        vs.sparse_attn_prefill(ck, Q, K, V, *sets, out=out, ws=ws_a, dca=dca)
         if ev: ev[3].record()
 
     for _ in range(args.warmup):
@@ -181,12 +187,12 @@ def main():
     if not args.no_dense and not w.dense:
         ws_d = torch.empty(max(vs.workspace_bytes(ck, vs.VS_WS_DENSE), 256), dtype=torch.uint8, device=dev)
         out_d = torch.empty_like(out)
-        vs.dense_causal_prefill(ck, Q, K, V, out=out_d, ws=ws_d)
+        vs.dense_causal_prefill(ck, Q, K, V, out=out_d, ws=ws_d, dca=dca)
         torch.cuda.synchronize()
         e = _events(2)
         e[0].record()
         for _ in range(2):
-            vs.dense_causal_prefill(ck, Q, K, V, out=out_d, ws=ws_d)
+            vs.dense_causal_prefill(ck, Q, K, V, out=out_d, ws=ws_d, dca=dca)
         e[1].record()
         torch.cuda.synchronize()
         dense_ms = e[0].elapsed_time(e[1]) / 2
@@ -221,20 +227,25 @@ def main():
             cki = vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, Ci, si, w.softmax_scale, last_q=w.last_q,
                            vertical_budget=bv, slash_budget=bs, keep_first_cols=w.keep_first_cols,
                            keep_local_band=w.keep_local_band)
-            Qi = vsgen.make_q(w, si, si + Ci, device=dev)
+            dca_i = None
+            if w.dca_chunk > 0:
+                Qi, qs_i, qi_i = vsgen.make_q_dca(w, si, si + Ci, device=dev)
+                dca_i = (qs_i, qi_i, w.dca_chunk, w.dca_window)
+            else:
+                Qi = vsgen.make_q(w, si, si + Ci, device=dev)
             nki = si + Ci
             vsc_i, ssc_i = vscore[:, :nki].contiguous(), sscore[:, :nki].contiguous()
             oi = out_l[:Ci]
             e = _events(4)
             torch.cuda.synchronize()
             e[0].record()
-            vs.estimate(cki, Qi, K, vscore=vsc_i, sscore=ssc_i, ws=ws_e_l)
+            vs.estimate(cki, Qi, K, vscore=vsc_i, sscore=ssc_i, ws=ws_e_l, dca=dca_i)
             vs.select(cki, vsc_i, ssc_i, sets=sets)
             e[1].record()
-            vs.sparse_attn_prefill(cki, Qi, K, V, *sets, out=oi, ws=ws_a_l)
+            vs.sparse_attn_prefill(cki, Qi, K, V, *sets, out=oi, ws=ws_a_l, dca=dca_i)
             e[2].record()
             if not args.no_dense:
-                vs.dense_causal_prefill(cki, Qi, K, V, out=oi, ws=ws_a_l)
+                vs.dense_causal_prefill(cki, Qi, K, V, out=oi, ws=ws_a_l, dca=dca_i)
             e[3].record()
             torch.cuda.synchronize()
             tl = vs.count_tiles(cki, *sets).sum().item()
@@ -264,7 +275,7 @@ def main():
             sets_h = (allv, np.ones(w.n_q_heads, np.int32), allv.copy(), np.ones(w.n_q_heads, np.int32))
         else:
             sets_h = tuple(x.cpu().numpy() for x in sets)
-        cpu = cpu_baseline(w, pbk, Q, K, V, sets_h, args.cpu_seconds)
+        cpu = cpu_baseline(w, pbk, Q, K, V, sets_h, args.cpu_seconds, dca=dca)
 
     res = {
         "metric": "ms per 32K prefill chunk at 1M ctx (estimate + select + block-sparse attention)",

@@ -210,6 +210,11 @@ int vs_dense_causal_prefill_dca(const vs_params *p, const void *q_intra, const v
 int vs_estimate_dca(const vs_params *p, const void *q_intra, const vs_dca *dca, const void *k,
                     float *vscore, float *sscore, float *lse_lastq, void *ws, size_t ws_bytes,
                     void *stream);
+/* vs_prefill_chunk with DCA: the estimate takes the rotations of dca_select (null: those of
+ * dca), the attention those of dca; both share q_intra. */
+int vs_prefill_chunk_dca(const vs_params *p, const void *q_intra, const vs_dca *dca,
+                         const vs_dca *dca_select, const void *k, const void *v, void *out,
+                         float *lse, void *ws, size_t ws_bytes, void *stream);
 
 /* Cost model and chunk planner (host functions; sec. 6.3 "Dynamic Chunked Pipeline
  * Parallelism": chunk sizes are adjusted to the complexity of the attention

@@ -97,7 +97,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
            "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step",
-           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca", "vs_estimate_dca"]
+           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca", "vs_estimate_dca", "vs_prefill_chunk_dca"]
 
 
 def status_string(status: int) -> str:
@@ -346,8 +346,10 @@ def dense_causal_prefill(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None, 
     return out, lse
 
 
-def prefill_chunk(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None):
-    """vs_prefill_chunk: estimate -> select -> sparse attention on the current stream."""
+def prefill_chunk(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None, dca=None, dca_select=None):
+    """vs_prefill_chunk: estimate -> select -> sparse attention on the current stream; with
+    dca = (q_succ, q_inter, chunk, window) vs_prefill_chunk_dca (dca_select: the rotations the
+    estimate uses, default those of dca)."""
     for t, nm in ((q, "q"), (k, "k"), (v, "v")):
         _chk_inner(t, nm, ck.head_dim)
     assert q.shape[0] == ck.q_len and k.shape[0] >= ck.n_k and v.shape[0] >= ck.n_k
@@ -359,6 +361,13 @@ def prefill_chunk(ck: Chunk, q, k, v, want_lse=False, out=None, ws=None):
     if ws is None:
         ws = torch.empty(max(n, 256), dtype=torch.uint8, device=dev)
     p = ck.params(q=q, k=k, v=v, out=out)
+    if dca is not None:
+        d = _dca_struct(ck, q, dca)
+        ds = _dca_struct(ck, q, dca_select) if dca_select is not None else None
+        _check(lib().vs_prefill_chunk_dca(C.byref(p), _ptr(q), C.byref(d), C.byref(ds) if ds is not None else None,
+                                          _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()),
+               "vs_prefill_chunk_dca")
+        return out, lse
     _check(lib().vs_prefill_chunk(C.byref(p), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), _ptr(ws),
                                   ws.numel(), _stream()), "vs_prefill_chunk")
     return out, lse

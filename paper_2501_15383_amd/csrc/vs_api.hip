@@ -326,8 +326,10 @@ int vs_dense_causal_prefill_dca(const vs_params* p, const void* q_intra, const v
   return dense_attn(p, q_intra, dca, k, v, out, lse, ws, ws_bytes, stream);
 }
 
-int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const void* v, void* out,
-                     float* lse, void* ws, size_t ws_bytes, void* stream) {
+namespace {
+// dca == null: plain.  sel: the rotations the estimate uses (null: those of dca).
+int prefill_chunk_any(const vs_params* p, const void* q, const vs_dca* dca, const vs_dca* sel, const void* k,
+                      const void* v, void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_params(p, true);
   if (rc != VS_OK) return rc;
   if (!q || !k || !v || !out) return VS_ERR_INVALID_ARG;
@@ -344,11 +346,24 @@ int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const voi
   int32_t* s_cnt = (int32_t*)(b + w.s_cnt);
   void* sub = b + w.sub;
   const size_t sub_bytes = w.total - w.sub;
-  rc = vs_estimate(p, q, k, vscore, sscore, nullptr, sub, sub_bytes, stream);
+  rc = estimate_any(p, q, dca ? (sel ? sel : dca) : nullptr, k, vscore, sscore, nullptr, sub, sub_bytes, stream);
   if (rc != VS_OK) return rc;
   rc = vs_select(p, vscore, sscore, v_idx, v_cnt, s_idx, s_cnt, sub, sub_bytes, stream);
   if (rc != VS_OK) return rc;
-  return vs_sparse_attn_prefill(p, q, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse, sub, sub_bytes, stream);
+  return sparse_attn(p, q, dca, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse, sub, sub_bytes, stream);
+}
+}  // namespace
+
+int vs_prefill_chunk(const vs_params* p, const void* q, const void* k, const void* v, void* out,
+                     float* lse, void* ws, size_t ws_bytes, void* stream) {
+  return prefill_chunk_any(p, q, nullptr, nullptr, k, v, out, lse, ws, ws_bytes, stream);
+}
+
+int vs_prefill_chunk_dca(const vs_params* p, const void* q_intra, const vs_dca* dca, const vs_dca* dca_select,
+                         const void* k, const void* v, void* out, float* lse, void* ws, size_t ws_bytes,
+                         void* stream) {
+  if (!dca) return VS_ERR_INVALID_ARG;
+  return prefill_chunk_any(p, q_intra, dca, dca_select, k, v, out, lse, ws, ws_bytes, stream);
 }
 
 int vs_count_tiles(const vs_params* p, const int32_t* v_idx, const int32_t* v_cnt,

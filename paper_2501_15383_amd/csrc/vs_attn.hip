@@ -458,6 +458,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // K Q^T of a masked tile, of the first tile of a row block, or of a tile whose scores
   // outran the reference: true maximum first, then the exponentials.  Nothing may be pending
   // (the accumulators must be up to date when the reference moves).  Leaves the tile pending.
+  // DCA: first key block of the chunk that holds this wave's query block
+  const int dca_cs = DCA ? ((m0 + t) / a.dca_cblk) * a.dca_cblk : 0;
   int need_var = 0;       // DCA: rotation this wave's tile needs; 3 = it differs inside the tile (codes in dcak_s)
   uint32_t dca_need = 0;  //      need_var == 3: bit v set iff some usable element needs rotation v
   bool qsw = false;       //      the registers hold another rotation than the tile needs
@@ -697,13 +699,12 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       // the local window, the successive-chunk one; all others the inter-chunk one
       qsw = false;
       if (part) {
-        const int m = m0 + t, cq = m / a.dca_cblk;
         if (cur_kind == 0) {
           const int dblk = cur_idx - (NQB - 1) + t;  // block distance, >= 0 for a tile this wave takes
-          const int ck = (m - dblk) / a.dca_cblk;
-          if (ck == cq) need_var = 0;
-          else if (ck == cq - 1 && dblk < a.dca_wblk) need_var = 1;
-          else if (ck == cq - 1 && dblk == a.dca_wblk) {
+          const int cb = m0 + t - dblk;               // the key block
+          if (cb >= dca_cs) need_var = 0;
+          else if (cb >= dca_cs - a.dca_cblk && dblk < a.dca_wblk) need_var = 1;
+          else if (cb >= dca_cs - a.dca_cblk && dblk == a.dca_wblk) {
             // the window ends inside this block: distance 64 dblk + il - r < window iff il < r
             need_var = 3;
             dca_need = 6u;
@@ -711,12 +712,12 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
           } else need_var = 2;
         } else {
           const int j = vidx_s[buf * 64 + lane];
-          const int ck = (j >> 6) / a.dca_cblk;
+          const int cb = j >> 6;
           int code = 0;
-          if (ck == cq) code = 100;
-          else if (ck == cq - 1) {
-            const int64_t thr = 64 * (int64_t)a.dca_wblk - (64 * (int64_t)m - j);  // il < thr: inside the window
-            code = thr < 0 ? 0 : (thr > 64 ? 64 : (int)thr);
+          if (cb >= dca_cs) code = 100;
+          else if (cb >= dca_cs - a.dca_cblk) {
+            const int thr = 64 * a.dca_wblk - (64 * (m0 + t) - j);  // il < thr: inside the window
+            code = thr < 0 ? 0 : (thr > 64 ? 64 : thr);
           }
           dcak_s[wv * 64 + lane] = (uint8_t)code;
           dca_need = (__ballot(usable && code == 100) != 0 ? 1u : 0u) |
@@ -725,6 +726,12 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
           need_var = 3;
         }
         qsw = need_var != q_var;
+        if (qsw && cur_kind == 0) {
+          // a slash tile that needs another rotation takes the path of the masked tiles, with
+          // a mask that lets every row use every key
+          vert = true;
+          need_s[wv * 64 + lane] = 0;
+        }
       }
     }
   };
@@ -748,7 +755,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   for (;;) {
     classify();
     // steady state: runs of steps in which this wave multiplies tile i and folds in tile i - 1
-    while (__builtin_expect(pend && part && !(diag || vert || !have_max) && !(DCA && qsw), 1)) {
+    while (__builtin_expect(pend && part && !(diag || vert || !have_max), 1)) {
       if (__builtin_expect(!fused(kb, vbp, launch_copies), 0)) qk_exact(kb, diag, vert, apply_mask);
       end_step();
       classify();
@@ -757,10 +764,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     if (pend) drain(vbp);
     bool exact = diag || vert || !have_max;
     if constexpr (DCA) {
-      if (part && qsw) {
-        if (need_var < 3) load_q(need_var);
-        else exact = true;
-      }
+      if (part && qsw && need_var < 3) load_q(need_var);
     }
     if (part && !exact) exact = !qk_fast(kb);
     if (__builtin_expect(part && exact, 0)) qk_exact(kb, diag, vert, apply_mask);

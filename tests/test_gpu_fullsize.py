@@ -37,21 +37,27 @@ def _run_sparse_chunk(name, chunk_index, heads, n_rows, seed):
     C, n_k = w.chunk, s + w.chunk
     dev = torch.device("cuda:0")
     K, V = vsgen.make_kv(w, n_k, device=dev)
-    Q = vsgen.make_q(w, s, s + C, device=dev)
+    dca = odca = None   # workloads with Dual Chunk Attention positions: three rotations of the queries
+    if w.dca_chunk > 0:
+        Q, q_succ, q_inter = vsgen.make_q_dca(w, s, s + C, device=dev)
+        dca = (q_succ, q_inter, w.dca_chunk, w.dca_window)
+        odca = oracle.Dca(w.dca_chunk, w.dca_window, vsgen.as_u16(q_succ), vsgen.as_u16(q_inter))
+    else:
+        Q = vsgen.make_q(w, s, s + C, device=dev)
     pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, last_q=w.last_q,
                         vertical_budget=w.vertical_budget, slash_budget=w.slash_budget,
                         keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
     ck = chunk_of(pb)
-    vsc, ssc, lse_w = vs.estimate(ck, Q, K, want_lse=True)
+    vsc, ssc, lse_w = vs.estimate(ck, Q, K, want_lse=True, dca=dca)
     sets = vs.select(ck, vsc, ssc)
-    out, lse = vs.sparse_attn_prefill(ck, Q, K, V, *sets, want_lse=True)
-    out2, _ = vs.prefill_chunk(ck, Q, K, V)
+    out, lse = vs.sparse_attn_prefill(ck, Q, K, V, *sets, want_lse=True, dca=dca)
+    out2, _ = vs.prefill_chunk(ck, Q, K, V, dca=dca)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "vs_prefill_chunk differs from its stages"
 
     qh, kh, vh = vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V)
     # ---- estimation and selection of the sampled heads against the oracle
-    rvs, rss, rlse = oracle.estimate(pb, qh, kh, heads=heads)
+    rvs, rss, rlse = oracle.estimate(pb, qh, kh, heads=heads, dca=odca)
     gv, gs = f64(vsc[heads]), f64(ssc[heads])
     np.testing.assert_allclose(f64(lse_w[heads]), rlse, atol=5e-4, rtol=0)
     np.testing.assert_allclose(gv.sum(1), min(w.last_q, C), rtol=2e-4)
@@ -64,11 +70,11 @@ def _run_sparse_chunk(name, chunk_index, heads, n_rows, seed):
         check_index_sets(rss[i], sets_h[2][h], sets_h[3][h], w.slash_budget, w.keep_local_band, f"{name} head {h} slash")
     # ---- attention of sampled rows: the oracle is fed the GPU's own index sets
     rows = _sample_rows(np.random.default_rng(seed), C, n_rows)
-    ref_out, ref_lse = oracle.sparse_attention(pb, qh, kh, vh, *sets_h, heads=heads, rows=rows)
+    ref_out, ref_lse = oracle.sparse_attention(pb, qh, kh, vh, *sets_h, heads=heads, rows=rows, dca=odca)
     _check_rows(out, lse, ref_out, ref_lse, heads, rows, f"{name} chunk {ci}")
     # ---- at any size: weights of every row sum to one (V == 1 gives out == 1)
     ones = torch.ones_like(V)
-    o1, _ = vs.sparse_attn_prefill(ck, Q, K, ones, *sets)
+    o1, _ = vs.sparse_attn_prefill(ck, Q, K, ones, *sets, dca=dca)
     torch.cuda.synchronize()
     dev1 = (o1.float() - 1.0).abs().max().item()
     assert dev1 < 1e-2, f"{name}: rows of P do not sum to one ({dev1})"
@@ -127,3 +133,10 @@ def test_sparse_7b_1m_middle_chunk():
 
 def test_sparse_14b_1m_last_chunk():
     _run_sparse_chunk("14b_1m", -1, heads=[7, 38], n_rows=8, seed=5)            # configuration 4
+
+
+def test_sparse_7b_1m_dca_chunks():
+    # Dual Chunk Attention positions (chunks of 256K): the last prefill chunk meets keys of all three
+    # patterns; prefill chunk 8 starts a DCA chunk, so its rows cross the end of the local window
+    _run_sparse_chunk("7b_1m_dca", -1, heads=[5, 22], n_rows=8, seed=6)
+    _run_sparse_chunk("7b_1m_dca", 8, heads=[16], n_rows=8, seed=7)

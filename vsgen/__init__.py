@@ -23,6 +23,13 @@ Extra, not one of the five configurations ("7b_1m_local"): before RoPE a shared 
 vector (per KV head, length local_mag) is added to every query and key, so that q_i . k_j
 gains a term that depends only on i - j and decays slowly with it -- slash lines that
 cluster at small offsets, as the attention maps of trained models show them.
+Extra ("7b_1m_dca"): the positions fed to RoPE are those of Dual Chunk Attention (section
+5.1) with chunk length c = dca_chunk and local window dca_window: a key at position j is
+rotated at j mod c; the queries come in three rotations, at i mod c (intra-chunk), at
+(i mod c) + c (successive-chunk: against a key of the chunk before, the difference is the true
+distance i - j) and at the constant c + dca_window - 1 (inter-chunk: no relative position
+exceeds what one chunk plus the window has seen).  Only the positions differ; which rotation
+meets which key is decided by the library and the oracle, not here.
 """
 from __future__ import annotations
 
@@ -57,6 +64,8 @@ class Workload:
     sink_mag_per_head: bool = False
     heavy_tail: bool = False
     local_mag: float = 0.0     # > 0: planted slash structure (see the module docstring)
+    dca_chunk: int = 0         # > 0: Dual Chunk Attention positions (see the module docstring)
+    dca_window: int = 0
     rope_theta: float = 1.0e7
     config_id: int = 0
     seed: int = BASE_SEED
@@ -87,6 +96,11 @@ WORKLOADS = {
     # extra: the 7B configuration with planted, clustered slash lines (not a BASELINE configuration)
     "7b_1m_local": Workload("7b_1m_local", 28, 4, 128, 1048576, 32768, vertical_budget=1000,
                             slash_budget=6096, n_sink=256, sink_mag_per_head=True, local_mag=8.0, config_id=5),
+    # extra: the 7B configuration with Dual Chunk Attention positions (chunks of 256K tokens, four of
+    # them in 1M; the local window is not given in the paper, 8192 is this recipe's choice)
+    "7b_1m_dca": Workload("7b_1m_dca", 28, 4, 128, 1048576, 32768, vertical_budget=1000,
+                          slash_budget=6096, n_sink=256, sink_mag_per_head=True, dca_chunk=262144,
+                          dca_window=8192, config_id=6),
 }
 
 
@@ -142,11 +156,15 @@ def _counters(t0: int, t1: int, n_heads: int, d: int, device) -> torch.Tensor:
     return (t * n_heads + h) * d + e
 
 
-def _rope(x: torch.Tensor, t0: int, theta: float) -> torch.Tensor:
-    """Half-split rotary embedding at absolute positions t0.. (fp64 angles)."""
+def _rope(x: torch.Tensor, t0, theta: float) -> torch.Tensor:
+    """Half-split rotary embedding (fp64 angles) at absolute positions t0, t0 + 1, ... when t0 is
+    an int, or at the positions given by an int64 tensor [n]."""
     n, _, d = x.shape
     half = d // 2
-    pos = torch.arange(t0, t0 + n, dtype=torch.float64, device=x.device).view(-1, 1, 1)
+    if isinstance(t0, torch.Tensor):
+        pos = t0.to(torch.float64).view(-1, 1, 1)
+    else:
+        pos = torch.arange(t0, t0 + n, dtype=torch.float64, device=x.device).view(-1, 1, 1)
     inv = theta ** (-torch.arange(half, dtype=torch.float64, device=x.device) * 2.0 / d)
     ang = pos * inv.view(1, 1, -1)
     c, s = torch.cos(ang).to(torch.float32), torch.sin(ang).to(torch.float32)
@@ -206,16 +224,32 @@ def _to_bf16(x: torch.Tensor) -> torch.Tensor:
     return x.to(torch.bfloat16)
 
 
-def make_q(w: Workload, t0: int, t1: int, device="cpu") -> torch.Tensor:
-    """Queries of tokens t0..t1-1: bf16 [t1-t0][Hq][D]."""
+def _make_q_at(w: Workload, t0: int, t1: int, positions, device) -> torch.Tensor:
     x = _normal(_counters(t0, t1, w.n_q_heads, w.head_dim, device), _key(w.seed, w.config_id, _T_Q, 0))
     g_of_h = torch.arange(w.n_q_heads, device=device) // (w.n_q_heads // w.n_kv_heads)
     if w.local_mag > 0:
         x = x + w.local_mag * local_vectors(w, device)[g_of_h].unsqueeze(0)
-    x = _rope(x, t0, w.rope_theta)
+    x = _rope(x, positions, w.rope_theta)
     if w.n_sink > 0:
         x = x + unit_vectors(w, device)[g_of_h].unsqueeze(0)
     return _to_bf16(x)
+
+
+def make_q(w: Workload, t0: int, t1: int, device="cpu") -> torch.Tensor:
+    """Queries of tokens t0..t1-1: bf16 [t1-t0][Hq][D] (with DCA positions: the intra-chunk rotation)."""
+    if w.dca_chunk > 0:
+        return make_q_dca(w, t0, t1, device)[0]
+    return _make_q_at(w, t0, t1, t0, device)
+
+
+def make_q_dca(w: Workload, t0: int, t1: int, device="cpu"):
+    """The three rotations of the queries of tokens t0..t1-1 under Dual Chunk Attention:
+    (intra-chunk, successive-chunk, inter-chunk), each bf16 [t1-t0][Hq][D]."""
+    assert w.dca_chunk > 0
+    i = torch.arange(t0, t1, dtype=torch.int64, device=device)
+    return (_make_q_at(w, t0, t1, i % w.dca_chunk, device),
+            _make_q_at(w, t0, t1, i % w.dca_chunk + w.dca_chunk, device),
+            _make_q_at(w, t0, t1, torch.full_like(i, w.dca_chunk + w.dca_window - 1), device))
 
 
 def _make_kv_slab(w: Workload, t0: int, t1: int, device, sinks, mags, u):
@@ -229,7 +263,10 @@ def _make_kv_slab(w: Workload, t0: int, t1: int, device, sinks, mags, u):
         k = k * torch.where(pick, torch.exp(z), torch.ones_like(z))
     if w.local_mag > 0:
         k = k + w.local_mag * local_vectors(w, device).unsqueeze(0)
-    k = _rope(k, t0, w.rope_theta)
+    if w.dca_chunk > 0:
+        k = _rope(k, torch.arange(t0, t1, dtype=torch.int64, device=device) % w.dca_chunk, w.rope_theta)
+    else:
+        k = _rope(k, t0, w.rope_theta)
     for g in range(w.n_kv_heads):
         pos = sinks[g]
         pos = pos[(pos >= t0) & (pos < t1)].to(device) - t0
