@@ -91,12 +91,15 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
   const int64_t pos_lo = a.p0 + 32 * ib, pos_hi = pos_lo + 31;
   const int64_t cq_lo = DCA ? pos_lo / dca_c : 0, cq_hi = DCA ? pos_hi / dca_c : 0;
   const int64_t dca_bound = (cq_lo + 1) * dca_c;
-  // pattern of (window row r of this wave's half, key j) for a tile whose keys lie in chunk ck
-  auto var_of = [&](int64_t ck, int r_in_half, int64_t j) -> int {
-    const int64_t pos = pos_lo + r_in_half;
-    const int64_t cq = cq_lo + (pos >= dca_bound ? 1 : 0);
-    if (ck == cq) return 0;
-    if (ck == cq - 1 && pos - j < a.dca_window) return 1;
+  // rows of this half at or past row_bound lie in the next chunk (32: none of them)
+  const int row_bound = DCA && dca_bound - pos_lo < 32 ? (int)(dca_bound - pos_lo) : 32;
+  const int win32 = DCA ? (int)(a.dca_window < (1 << 30) ? a.dca_window : (1 << 30)) : 0;
+  // pattern of (row r of this wave's half, key j0 + jrel) for a tile whose keys lie ck_rel chunks
+  // after the chunk of the half's first row, and whose first key is dist0 tokens before that row
+  auto var_of = [&](int ck_rel, int dist0, int r_in_half, int jrel) -> int {
+    const int cq = r_in_half >= row_bound ? 1 : 0;
+    if (ck_rel == cq) return 0;
+    if (ck_rel == cq - 1 && dist0 + r_in_half - jrel < win32) return 1;
     return 2;
   };
 
@@ -155,9 +158,13 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
 
     // DCA: which rotation(s) this wave's rows need against the keys of this tile (all in chunk ck)
     uint32_t need = 1u;
-    int64_t ck = 0;
+    int ck_rel = 0, dist0 = 0;
     if constexpr (DCA) {
-      ck = j0 / dca_c;
+      const int64_t ck = j0 / dca_c;
+      const int64_t rel = ck - cq_lo;  // <= 1 for causal keys; far chunks all count as "earlier than the one before"
+      ck_rel = rel < -2 ? -2 : (int)rel;
+      const int64_t d0 = pos_lo - j0;  // < 2^31 by the limit on the number of keys
+      dist0 = d0 < -(1 << 30) ? -(1 << 30) : (int)d0;
       if (cq_lo == cq_hi) {
         if (ck == cq_lo) need = 1u;
         else if (ck == cq_lo - 1) {
@@ -201,7 +208,7 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
                 tt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], tt, 0, 0, 0);
 #pragma unroll
               for (int x = 0; x < 16; ++x)
-                if (var_of(ck, lane & 31, j0 + 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3)) == var) s[x] = tt[x];
+                if (var_of(ck_rel, dist0, lane & 31, 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3)) == var) s[x] = tt[x];
             }
           } else {
 #pragma unroll
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
                 tt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[st], *(const bf16x8*)(kfp + 16 * st), tt, 0, 0, 0);
 #pragma unroll
               for (int x = 0; x < 16; ++x)
-                if (var_of(ck, 8 * (x >> 2) + 4 * hh + (x & 3), j0 + 32 * jb + (lane & 31)) == var) s[x] = tt[x];
+                if (var_of(ck_rel, dist0, 8 * (x >> 2) + 4 * hh + (x & 3), 32 * jb + (lane & 31)) == var) s[x] = tt[x];
             }
           } else
 #pragma unroll
