@@ -82,6 +82,10 @@ def main():
     ap.add_argument("--n-ctx", type=int, default=0, help="override the context length (tokens)")
     ap.add_argument("--segment-blocks", type=int, default=0,
                     help="64-key blocks per key segment of the sparse launch (0 = the library's choice)")
+    ap.add_argument("--chunk-rows", type=int, default=0,
+                    help="rows of the chunk (a multiple of 64) instead of the workload's 32768: short chunks at the end "
+                         "of a long context, the decode-side use of the kernels")
+    ap.add_argument("--key-split", type=int, default=0, help="VS_OPT_ATTN_KEY_SPLIT: 0 automatic, 1 never, n ranges")
     ap.add_argument("--layer-plan", choices=["equal", "dense", "sparse"], default="equal",
                     help="chunk boundaries of --layer: equal lengths, or vs_plan_chunks with that cost model")
     ap.add_argument("--layer", action="store_true",
@@ -109,6 +113,9 @@ def main():
     w = vsgen.WORKLOADS[args.workload]
     if args.n_ctx:
         w = vsgen.scaled(w, n_ctx=args.n_ctx)
+    if args.chunk_rows:
+        w = vsgen.scaled(w, chunk=args.chunk_rows)
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, args.key_split)
     ci = args.chunk_index % w.n_chunks
     s = ci * w.chunk
     C = min(w.chunk, w.n_ctx - s)
@@ -278,7 +285,8 @@ def main():
         cpu = cpu_baseline(w, pbk, Q, K, V, sets_h, args.cpu_seconds, dca=dca)
 
     res = {
-        "metric": "ms per 32K prefill chunk at 1M ctx (estimate + select + block-sparse attention)",
+        "metric": ("ms per 32K prefill chunk at 1M ctx (estimate + select + block-sparse attention)" if not args.chunk_rows
+                   and not args.n_ctx else f"ms per {C}-row chunk at {n_k} keys (estimate + select + block-sparse attention)"),
         "value": gpu_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": gpu_ms, "wall_ms_per_step": wall_ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",

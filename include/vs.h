@@ -244,8 +244,14 @@ int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model,
  *     other (bounded waits on counters in the workspace) so that their K/V
  *     blocks are shared through the L2.  Only the timing depends on it.  The
  *     choice changes VS_WS_SPARSE / VS_WS_DENSE / VS_WS_CHUNK sizes, so set it
- *     before asking for them. */
-enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0 };
+ *     before asking for them.
+ *   VS_OPT_ATTN_KEY_SPLIT  chunks with few (query tile, head) units (a decode step, a short
+ *     last chunk) have their key walk cut into ranges, one workgroup each, and a second
+ *     kernel folds the partial results: 0 = automatic (up to 16 ranges, so that about 512
+ *     workgroups run), 1 = never, 2..16 = that many ranges (at least 16 key blocks each).
+ *     Results agree within the rounding of the fp32 partial sums.  Changes the workspace
+ *     sizes like the option above. */
+enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0, VS_OPT_ATTN_KEY_SPLIT = 1 };
 int vs_set_option(int which, int64_t value);
 
 #ifdef __cplusplus

@@ -44,7 +44,9 @@ int check_ws(const void* ws, size_t have, size_t need) {
   return VS_OK;
 }
 
-size_t sparse_ws_bytes(const vs_params& p, bool dense) { return blocklist_bytes(p, dense) + attn_sync_bytes(p); }
+size_t sparse_ws_bytes(const vs_params& p, bool dense) {
+  return blocklist_bytes(p, dense) + attn_sync_bytes(p) + attn_split_bytes(p);
+}
 
 // layout of the VS_WS_CHUNK workspace
 struct ChunkWs {
@@ -162,6 +164,10 @@ int vs_set_option(int which, int64_t value) {
       if (value < 0 || value > (int64_t)INT32_MAX) return VS_ERR_INVALID_ARG;
       set_attn_segment_blocks((int)value);
       return VS_OK;
+    case VS_OPT_ATTN_KEY_SPLIT:
+      if (value < 0 || value > 16) return VS_ERR_INVALID_ARG;
+      set_attn_key_split((int)value);
+      return VS_OK;
     default: return VS_ERR_INVALID_ARG;
   }
 }
@@ -276,8 +282,9 @@ int sparse_attn(const vs_params* p, const void* q, const vs_dca* dca, const void
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_build_blocklist(*p, s_idx, s_cnt, false, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, dca ? &da : nullptr, k, v, v_idx, v_cnt, false, bl, out, lse,
-                                     (char*)ws + blocklist_bytes(*p, false), st));
+  char* sync = (char*)ws + blocklist_bytes(*p, false);
+  return hip_status(launch_attention(*p, q, dca ? &da : nullptr, k, v, v_idx, v_cnt, false, bl, out, lse, sync,
+                                     sync + attn_sync_bytes(*p), st));
 }
 
 int dense_attn(const vs_params* p, const void* q, const vs_dca* dca, const void* k, const void* v,
@@ -294,8 +301,9 @@ int dense_attn(const vs_params* p, const void* q, const vs_dca* dca, const void*
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = launch_build_blocklist(*p, nullptr, nullptr, true, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
-  return hip_status(launch_attention(*p, q, dca ? &da : nullptr, k, v, nullptr, nullptr, true, bl, out, lse,
-                                     (char*)ws + blocklist_bytes(*p, true), st));
+  char* sync = (char*)ws + blocklist_bytes(*p, true);
+  return hip_status(launch_attention(*p, q, dca ? &da : nullptr, k, v, nullptr, nullptr, true, bl, out, lse, sync,
+                                     sync + attn_sync_bytes(*p), st));
 }
 }  // namespace
 

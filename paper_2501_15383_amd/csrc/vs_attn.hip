@@ -41,6 +41,13 @@ struct AttnArgs {
   const __bf16* q_succ;
   const __bf16* q_inter;
   int32_t dca_cblk, dca_wblk;
+  // Key split (template parameter SPLIT) for chunks with few query tiles: the walk of a (tile,
+  // head) is cut into n_split ranges of key-block distances, one workgroup each; every
+  // workgroup writes its unnormalised result (relative to its own reference) and k_attn_combine
+  // folds them.  part_o [n_split][Hq][q_len][D], part_ml [n_split][Hq][q_len][2] (reference, sum)
+  int32_t n_split;
+  float* part_o;
+  float* part_ml;
   const __bf16* k;
   const __bf16* v;
   __bf16* out;
@@ -110,7 +117,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int D, int NQB, bool DCA>
+template <int D, int NQB, bool DCA, bool SPLIT>
 __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   constexpr int DCH = D / 8;           // 16-byte chunks per row
   constexpr int DSTEPS = D / 16;       // MFMA k-steps of QK^T
@@ -151,13 +158,23 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // Waiting is bounded and only shapes the timing: results never depend on it.
   const int grp = blockIdx.x & 7, member = blockIdx.x >> 3;
   const int n_full_gr = a.n_full * a.n_q_heads;   // full rounds: latest chunks first, heads inside
-  const int n_gr = n_full_gr + (a.n_rem * a.n_q_heads + a.members - 1) / a.members;
+  const int n_gr = SPLIT ? (a.n_qtiles * a.n_split * a.n_q_heads + a.members - 1) / a.members
+                         : n_full_gr + (a.n_rem * a.n_q_heads + a.members - 1) / a.members;
   uint32_t* const arr = a.arrive + (int64_t)grp * a.n_sync;
   const int s_glob_top = (int)((n_k - 1) / 64) / a.sync_blocks;  // highest sync segment of the chunk
   for (int rnd = 0; rnd * 8 + grp < n_gr; ++rnd) {
   const int gr = rnd * 8 + grp;
-  int h, qt;
-  if (gr < n_full_gr) {
+  int h, qt, sp = 0;
+  if constexpr (SPLIT) {
+    // unit u = ((head, tile), split), no pace keeping (the members walk different key ranges)
+    const int per_head = a.n_qtiles * a.n_split;
+    const int u = gr * a.members + member;
+    h = u / per_head;
+    const int v = u - h * per_head;
+    qt = h < a.n_q_heads ? v / a.n_split : a.n_qtiles;
+    sp = v % a.n_split;
+    if (h >= a.n_q_heads) h = 0;
+  } else if (gr < n_full_gr) {
     h = gr % a.n_q_heads;
     qt = a.n_rem + (a.n_full - 1 - gr / a.n_q_heads) * a.members + (a.members - 1 - member);
   } else {  // packed rounds: unit u = (head, tile below n_rem), tiles descending inside a head
@@ -174,6 +191,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   int seg_done = s_glob_top + 1;
   bool patient = true;  // a wait that ran out (group not co-resident?) ends the waiting for this tile
   auto enter_segment = [&](int s_new, bool wait) {
+    if constexpr (SPLIT) return;
     if (s_new >= seg_done - 1) return;  // still in the segment entered last
     if (wv == 0) {
       for (int sg = seg_done - 1 - lane; sg > s_new; sg -= 64) atomicAdd(&arr[sg], 1u);
@@ -258,28 +276,45 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // ---- tile iterator (uniform over the workgroup, kept in scalar registers) -----------------
   // kind 0: slash tile, idx = cc, mask = query blocks that use it; kind 1: vertical tile,
   // idx = vt; kind 2: end.  Entries are fetched 64 at a time (one per lane), one batch ahead.
-  uint32_t ecache = ent_h[lane], ecache_nx = ent_h[64 + lane];
-  int ei = -1;
+  // With a key split this workgroup walks the entries with cc in [cc_lo, cc_end] and every
+  // n_split-th vertical tile; the first entry is found by bisection (the list ascends in cc and
+  // ends in sentinels).
+  int cc_end = cc_last, ei0 = 0;
+  const int vstep = SPLIT ? a.n_split : 1;
+  if constexpr (SPLIT) {
+    const int per = (cc_last + a.n_split) / a.n_split;  // ceil((cc_last + 1) / n_split)
+    const int cc_lo = sp * per;
+    cc_end = cc_lo + per - 1 < cc_last ? cc_lo + per - 1 : cc_last;
+    int lo = 0, hi = (int)a.ent_len - 1;  // the last entry is a sentinel: an answer always exists
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      const int cm = (int)(__builtin_amdgcn_readfirstlane(ent_h[mid]) >> 4);
+      if (cm >= cc_lo) hi = mid; else lo = mid + 1;
+    }
+    ei0 = lo;
+  }
+  uint32_t ecache = ent_h[(ei0 & ~63) + lane], ecache_nx = ent_h[(ei0 & ~63) + 64 + lane];
+  int ei = ei0 - 1;
   auto advance = [&](int& kind, int& idx, int& mask) {
     int k2 = kind, i2 = idx, m2 = 0;
     if (k2 == 0) {
       ++ei;
-      if (__builtin_expect((ei & 63) == 0 && ei > 0, 0)) {
+      if (__builtin_expect((ei & 63) == 0 && ei > ei0, 0)) {
         ecache = ecache_nx;
         ecache_nx = ent_h[(ei & ~63) + 64 + lane];
       }
       const uint32_t e = __builtin_amdgcn_readlane(ecache, ei & 63);
       const int cc = (int)(e >> 4);
-      if (cc <= cc_last) {
+      if (cc <= cc_end) {
         i2 = cc; m2 = (int)(e & 15u);
         enter_segment((cc_last - cc) / a.sync_blocks, true);
       } else {
-        k2 = 1; i2 = -1;
+        k2 = 1; i2 = sp - vstep;
         enter_segment(-1, false);  // the slash walk is over
       }
     }
     if (k2 == 1) {
-      const int vt = i2 + 1;
+      const int vt = i2 + vstep;
       bool more = vt < n_vt;
       if (more) more = (int64_t)__builtin_amdgcn_readfirstlane(vidx_h[64 * vt]) <= last_pos;
       if (more) i2 = vt; else { k2 = 2; i2 = 0; }
@@ -775,6 +810,26 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // ---- normalise and store ------------------------------------------------------------------
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if constexpr (SPLIT) {
+    // this split's share of the row: accumulators and row sum relative to the reference m_o
+    if (row < a.q_len) {
+      const int64_t pr = ((int64_t)sp * a.n_q_heads + h) * a.q_len + row;
+      float* op = a.part_o + pr * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int vq = 0; vq < 4; ++vq) {
+          f32x4 o4;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) o4[x] = oacc[db][4 * vq + x];
+          *(f32x4*)(op + 32 * db + 8 * vq + 4 * hh) = o4;
+        }
+      if (hh == 0) {
+        a.part_ml[2 * pr] = m_o;
+        a.part_ml[2 * pr + 1] = l_tot;
+      }
+    }
+  } else
   if (row < a.q_len) {
     __bf16* op = a.out + row * a.o_stride_tok + (int64_t)h * a.o_stride_head;
 #pragma unroll
@@ -937,13 +992,69 @@ size_t attn_sync_bytes(const vs_params& p) {
   return align_up((size_t)8 * (size_t)ceil_div(n_blk, attn_sync_blocks(p)) * sizeof(uint32_t), 256);
 }
 
+// Key split of short chunks.  With few (query tile, head) units the persistent launch would
+// leave most of the chip idle, each unit walking the whole context alone; the walk is then cut
+// into n_split ranges.  The policy is fixed (512 workgroup slots: 256 compute units x 2), so
+// that workspace sizes do not depend on the device.
+static int g_key_split = 0;  // 0: automatic, 1: never, n: n ranges (still at least 16 key blocks each)
+void set_attn_key_split(int n) { g_key_split = n < 0 ? 0 : (n > 16 ? 16 : n); }
+int attn_split(const vs_params& p) {
+  if (g_key_split == 1) return 1;
+  const int64_t units = ceil_div(p.q_len, (int64_t)64 * kAttnQBlocks) * p.n_q_heads;
+  const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
+  int64_t s = g_key_split > 1 ? g_key_split : 512 / units;
+  if (s > 16) s = 16;
+  if (s > n_blk / 16) s = n_blk / 16;  // at least 16 key blocks per range
+  return s < 2 ? 1 : (int)s;
+}
+size_t attn_split_bytes(const vs_params& p) {
+  const int s = attn_split(p);
+  if (s == 1) return 0;
+  const size_t rows = (size_t)s * p.n_q_heads * (size_t)p.q_len;
+  return align_up(rows * p.head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256);
+}
+
+// out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s; one wave per (row, head),
+// splits folded in ascending order (fixed, so the result is run-to-run identical).
+template <int D>
+__global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int h = blockIdx.y;
+  if (row >= a.q_len) return;
+  float M = -INFINITY;
+  for (int sp = 0; sp < a.n_split; ++sp)
+    M = fmaxf(M, a.part_ml[2 * (((int64_t)sp * a.n_q_heads + h) * a.q_len + row)]);
+  float L = 0.f, acc[D / 64];
+#pragma unroll
+  for (int e = 0; e < D / 64; ++e) acc[e] = 0.f;
+  if (M != -INFINITY) {
+    for (int sp = 0; sp < a.n_split; ++sp) {
+      const int64_t pr = ((int64_t)sp * a.n_q_heads + h) * a.q_len + row;
+      const float m = a.part_ml[2 * pr];
+      if (m == -INFINITY) continue;
+      const float w = __builtin_amdgcn_exp2f(m - M);
+      L += a.part_ml[2 * pr + 1] * w;
+#pragma unroll
+      for (int e = 0; e < D / 64; ++e) acc[e] += a.part_o[pr * D + 64 * e + lane] * w;
+    }
+  }
+  const float inv = L > 0.f ? 1.0f / L : 0.f;
+  __bf16* op = a.out + row * a.o_stride_tok + (int64_t)h * a.o_stride_head;
+#pragma unroll
+  for (int e = 0; e < D / 64; ++e) op[64 * e + lane] = (__bf16)(acc[e] * inv);
+  if (a.lse && lane == 0)
+    a.lse[(int64_t)h * a.q_len + row] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
+}
+
 __global__ __launch_bounds__(256) void k_fill_zero_u32(uint32_t* p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
 hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
-                            const BlockList& bl, void* out, float* lse, void* sync_ws, hipStream_t st) {
+                            const BlockList& bl, void* out, float* lse, void* sync_ws, void* split_ws,
+                            hipStream_t st) {
   constexpr int NQB = kAttnQBlocks;
   if (!sync_ws) return hipErrorInvalidValue;
   AttnArgs a;
@@ -978,7 +1089,15 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   }
   int members = (2 * n_cu) / 8;
   if (members < 1) members = 1;
-  const int64_t units = (int64_t)a.n_qtiles * a.n_q_heads;
+  a.n_split = attn_split(p);
+  a.part_o = a.part_ml = nullptr;
+  if (a.n_split > 1) {
+    if (!split_ws) return hipErrorInvalidValue;
+    const size_t rows = (size_t)a.n_split * p.n_q_heads * (size_t)p.q_len;
+    a.part_o = (float*)split_ws;
+    a.part_ml = (float*)((char*)split_ws + align_up(rows * p.head_dim * sizeof(float), 256));
+  }
+  const int64_t units = (int64_t)a.n_qtiles * a.n_q_heads * a.n_split;
   if (units < 8 * (int64_t)members) members = (int)ceil_div(units, 8);  // small launches: no idle workgroups
   a.members = members;
   a.n_wg = 8 * members;
@@ -992,11 +1111,15 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel
   static bool attr_set = false;
   if (!attr_set) {
-    const void* fns[4] = {reinterpret_cast<const void*>(&k_attention<128, NQB, false>),
-                          reinterpret_cast<const void*>(&k_attention<64, NQB, false>),
-                          reinterpret_cast<const void*>(&k_attention<128, NQB, true>),
-                          reinterpret_cast<const void*>(&k_attention<64, NQB, true>)};
-    for (int i = 0; i < 4; ++i) {
+    const void* fns[8] = {reinterpret_cast<const void*>(&k_attention<128, NQB, false, false>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, false>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, true, false>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, true, false>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, false, true>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, true>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, true, true>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, true, true>)};
+    for (int i = 0; i < 8; ++i) {
       const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
                                                i % 2 == 0 ? attn_lds_bytes<128>() : attn_lds_bytes<64>());
       if (e != hipSuccess) return e;
@@ -1004,12 +1127,25 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
     attr_set = true;
   }
   const dim3 grid((unsigned)a.n_wg), block(128 * NQB);
+  const bool split = a.n_split > 1;
+#define VS_ATTN_LAUNCH(DD, DCA_, SPLIT_) \
+  hipLaunchKernelGGL((k_attention<DD, NQB, DCA_, SPLIT_>), grid, block, attn_lds_bytes<DD>(), st, a)
   if (p.head_dim == 128) {
-    if (dca) hipLaunchKernelGGL((k_attention<128, NQB, true>), grid, block, attn_lds_bytes<128>(), st, a);
-    else hipLaunchKernelGGL((k_attention<128, NQB, false>), grid, block, attn_lds_bytes<128>(), st, a);
+    if (dca && split) VS_ATTN_LAUNCH(128, true, true);
+    else if (dca) VS_ATTN_LAUNCH(128, true, false);
+    else if (split) VS_ATTN_LAUNCH(128, false, true);
+    else VS_ATTN_LAUNCH(128, false, false);
   } else {
-    if (dca) hipLaunchKernelGGL((k_attention<64, NQB, true>), grid, block, attn_lds_bytes<64>(), st, a);
-    else hipLaunchKernelGGL((k_attention<64, NQB, false>), grid, block, attn_lds_bytes<64>(), st, a);
+    if (dca && split) VS_ATTN_LAUNCH(64, true, true);
+    else if (dca) VS_ATTN_LAUNCH(64, true, false);
+    else if (split) VS_ATTN_LAUNCH(64, false, true);
+    else VS_ATTN_LAUNCH(64, false, false);
+  }
+#undef VS_ATTN_LAUNCH
+  if (split) {
+    const dim3 cgrid((unsigned)ceil_div(p.q_len, 4), (unsigned)p.n_q_heads);
+    if (p.head_dim == 128) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(k_attn_combine<64>, cgrid, dim3(256), 0, st, a);
   }
   return hipGetLastError();
 }

@@ -68,11 +68,17 @@ struct DcaArgs {
   const void* q_inter;
   int64_t chunk, window;
 };
-// sync_ws: attn_sync_bytes(p) bytes of counters (zero-filled by the launch itself); dca may be null
+// sync_ws: attn_sync_bytes(p) bytes of counters (zero-filled by the launch itself); split_ws:
+// attn_split_bytes(p) bytes (may be null when that is 0); dca may be null
 hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
-                            const BlockList& bl, void* out, float* lse, void* sync_ws, hipStream_t st);
+                            const BlockList& bl, void* out, float* lse, void* sync_ws, void* split_ws,
+                            hipStream_t st);
 size_t attn_sync_bytes(const vs_params& p);
+// key split of short chunks: number of ranges (1 = none) and bytes of partial results
+int attn_split(const vs_params& p);
+void set_attn_key_split(int n);
+size_t attn_split_bytes(const vs_params& p);
 void set_attn_segment_blocks(int blocks);
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,
                               const BlockList& bl, int64_t* tiles, hipStream_t st);

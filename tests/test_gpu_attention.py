@@ -12,6 +12,15 @@ from helpers import rand_bf16
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[0, 1], ids=["key_split_auto", "key_split_off"])
+def _key_split(request):
+    """Every case runs with the key split of short chunks chosen automatically (most of these
+    small shapes then take it) and switched off (the kernel the full-size launches use)."""
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, request.param)
+    yield
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+
+
 def _rand_sets(rng, pb, nv, ns, force_cols=(), force_offs=()):
     """Random ascending index sets in the layout vs_select produces."""
     hq, n_k = pb.n_q_heads, pb.n_k

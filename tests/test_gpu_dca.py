@@ -15,6 +15,15 @@ from test_gpu_attention import _rand_sets, _t
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[0, 1], ids=["key_split_auto", "key_split_off"])
+def _key_split(request):
+    """Every case runs with the key split of short chunks chosen automatically (most of these
+    small shapes then take it) and switched off (the kernel the full-size launches use)."""
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, request.param)
+    yield
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+
+
 def _inputs(rng, hq, hkv, d, c, s):
     qs = [rand_bf16(rng, (c, hq, d)) for _ in range(3)]
     k = rand_bf16(rng, (s + c, hkv, d)); v = rand_bf16(rng, (s + c, hkv, d))
