@@ -57,6 +57,7 @@ struct AttnArgs {
   const uint32_t* bm_a;  // block-diagonal bitmap per head
   const uint32_t* ent;   // key-block entry list per head (see BlockList)
   int64_t bm_stride;     // words per head, 0 = one bitmap shared by all heads (dense)
+  int32_t bm_words;      // words of one bitmap row; its last word holds the head's segment shift
   int64_t ent_stride;    // entries per head, 0 = one list shared by all heads (dense)
   int64_t ent_len;       // entries of one list (sentinel padding included)
   const int32_t* v_idx;  // null: no vertical phase
@@ -219,6 +220,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int64_t last_pos = a.q_start + row0 + rows_in_tile - 1;
 
   const uint32_t* bmA = a.bm_a + (int64_t)h * a.bm_stride;
+  const int seg_shift = __builtin_amdgcn_readfirstlane((int)bmA[a.bm_words - 1]);  // sparser list, longer sync segments
   const uint32_t* ent_h = a.ent + (int64_t)h * a.ent_stride;
   const int32_t* vidx_h = a.v_idx ? a.v_idx + (int64_t)h * a.v_budget : nullptr;
   const int vcnt = a.v_idx ? __builtin_amdgcn_readfirstlane(a.v_cnt[h]) : 0;
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       const int cc = (int)(e >> 4);
       if (cc <= cc_end) {
         i2 = cc; m2 = (int)(e & 15u);
-        enter_segment((cc_last - cc) / a.sync_blocks, true);
+        enter_segment(((cc_last - cc) / a.sync_blocks) >> seg_shift, true);
       } else {
         k2 = 1; i2 = sp - vstep;
         enter_segment(-1, false);  // the slash walk is over
@@ -921,6 +923,15 @@ __global__ __launch_bounds__(256) void k_build_blocklist(const int32_t* s_idx, c
     __syncthreads();
   }
   for (int i = running + tid; i < ent_stride; i += 256) E[i] = kEntSentinel;
+  // The last word of the bitmap row (beyond every diagonal) tells the attention kernel how
+  // sparse the list is: sync segments of this head are 2^shift times the base size, so that a
+  // segment holds about as many listed key blocks as it would in a dense list.
+  if (tid == 0) {
+    const uint32_t n_ent = running > 0 ? running : 1u;
+    int shift = 0;
+    while (shift < 4 && ((uint32_t)n_blk >> (shift + 1)) >= n_ent) ++shift;
+    A[n_words - 1] = (uint32_t)shift;
+  }
 }
 
 // Issued-tile accounting, one workgroup per head: for every query block of the chunk, the
@@ -976,15 +987,16 @@ hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, cons
 }
 
 // Pace keeping of the persistent launch: key blocks per sync segment.  The members of a group
-// (one XCD) may be at most two segments apart, so three segments of K and V (64 KiB per block
-// at D = 128) should fit the 4 MiB L2 of an XCD next to Q and the block lists.  0 = automatic.
+// (one XCD) may be at most two segments apart, so about three segments of K and V (64 KiB per
+// block at D = 128) are live in the caches at a time.  0 = automatic: 64 blocks at D = 128
+// (measured best for full lists; sparse lists scale it up per head, see k_build_blocklist).
 static int g_sync_blocks = 0;
 void set_attn_segment_blocks(int blocks) { g_sync_blocks = blocks < 0 ? 0 : blocks; }
 static int attn_sync_blocks(const vs_params& p) {
   if (g_sync_blocks > 0) return g_sync_blocks;
   const int per_block = kBlock * p.head_dim * 2 * 2;  // K and V of one KV head
   int sb = 1;
-  while (sb * 2 * 3 * per_block <= (3 << 20)) sb *= 2;
+  while (sb * 2 * 3 * per_block <= (6 << 20)) sb *= 2;
   return sb;
 }
 size_t attn_sync_bytes(const vs_params& p) {
@@ -1070,6 +1082,7 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.o_stride_tok = p.o_stride_tok; a.o_stride_head = p.o_stride_head;
   a.bm_a = bl.bm_a; a.ent = bl.ent;
   a.bm_stride = dense ? 0 : bl.words;
+  a.bm_words = (int32_t)bl.words;
   a.ent_stride = dense ? 0 : bl.ent_stride;
   a.ent_len = bl.ent_stride;
   a.v_idx = dense ? nullptr : v_idx; a.v_cnt = dense ? nullptr : v_cnt;
