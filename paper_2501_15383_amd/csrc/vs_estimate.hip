@@ -18,6 +18,8 @@
 // bf16 MFMA (32x32x16) with fp32 accumulation; sweep A uses the K Q^T orientation (a lane
 // owns one query), sweep B the Q K^T orientation (a lane owns one key).  Both sweeps are
 // bound by the exponential (one per score, quarter rate), not by memory.
+#include <type_traits>
+
 #include "vs_common.h"
 
 namespace vs {
@@ -147,6 +149,7 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
     if (j < a.n_k) a.vscore[(int64_t)h * a.n_k + j] = col_prev + other;
   };
 
+  int64_t ck = DCA ? ja / dca_c : 0, ck_next = (ck + 1) * dca_c;
   load_tile(0);
   store_tile(0);
   __syncthreads();
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
     uint32_t need = 1u;
     int ck_rel = 0, dist0 = 0;
     if constexpr (DCA) {
-      const int64_t ck = j0 / dca_c;
+      if (j0 >= ck_next) { ++ck; ck_next += dca_c; }  // chunk of the tile's keys, without a division per tile
       const int64_t rel = ck - cq_lo;  // <= 1 for causal keys; far chunks all count as "earlier than the one before"
       ck_rel = rel < -2 ? -2 : (int)rel;
       const int64_t d0 = pos_lo - j0;  // < 2^31 by the limit on the number of keys
@@ -184,7 +187,12 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
 
     if (head_ok) {
       if (PASS == 1 && ib == 0 && tile > 0) flush_columns(tile - 1);
-      float col[2];
+      float col[2] = {0.f, 0.f};
+      // a tile whose pairs are of several patterns is taken once per rotation, each pass keeping
+      // the pairs of its own pattern (every sum below is additive over the passes)
+      // (the body exists twice, so that the common one-rotation tiles carry none of the pattern tests)
+      auto blocks = [&](auto masked, const int rot) {
+      constexpr bool MASKED = decltype(masked)::value;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
         const __bf16* const kfp = &Ks[buf][(32 * jb + (lane & 31)) * KS + 8 * hh];
@@ -193,27 +201,14 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
         for (int x = 0; x < 16; ++x) s[x] = 0.f;
         if (PASS == 0) {
           // D[j][i]: lane = query i, element x = key 32 jb + 8 (x/4) + 4 hh + (x%4)
-          if (multi) {
-            // one product per rotation; element x (key 32 jb + 8 (x/4) + 4 hh + (x%4)) of lane
-            // (row lane%32) keeps the product of its own pattern
 #pragma unroll
-            for (int var = 0; var < 3; ++var) {
-              if (!((need >> var) & 1u)) continue;
-              if (q_var != var) load_q(var);
-              f32x16 tt;
+          for (int st = 0; st < DSTEPS; ++st)
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], s, 0, 0, 0);
+          if (MASKED) {
+            // this pass holds rotation `rot`: pairs of another pattern are left to their own pass
 #pragma unroll
-              for (int x = 0; x < 16; ++x) tt[x] = 0.f;
-#pragma unroll
-              for (int st = 0; st < DSTEPS; ++st)
-                tt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], tt, 0, 0, 0);
-#pragma unroll
-              for (int x = 0; x < 16; ++x)
-                if (var_of(ck_rel, dist0, lane & 31, 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3)) == var) s[x] = tt[x];
-            }
-          } else {
-#pragma unroll
-            for (int st = 0; st < DSTEPS; ++st)
-              s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*(const bf16x8*)(kfp + 16 * st), qreg[st], s, 0, 0, 0);
+            for (int x = 0; x < 16; ++x)
+              if (var_of(ck_rel, dist0, lane & 31, 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3)) != rot) s[x] = -INFINITY;
           }
           if (need_mask) {
             // key j is masked for query r iff j - p0 > r; dr = r - (j0 - p0) - 32 jb - 4 hh
@@ -235,23 +230,6 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
           mrun = m_new;
         } else {
           // D[i][j]: lane = key j = 32 jb + lane%32, element x = query 32 ib + 8 (x/4) + 4 hh + (x%4)
-          if (multi) {
-            // as in sweep A; here a lane is key 32 jb + lane%32 and element x is row 8 (x/4) + 4 hh + (x%4)
-#pragma unroll
-            for (int var = 0; var < 3; ++var) {
-              if (!((need >> var) & 1u)) continue;
-              if (q_var != var) load_q(var);
-              f32x16 tt;
-#pragma unroll
-              for (int x = 0; x < 16; ++x) tt[x] = 0.f;
-#pragma unroll
-              for (int st = 0; st < DSTEPS; ++st)
-                tt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qreg[st], *(const bf16x8*)(kfp + 16 * st), tt, 0, 0, 0);
-#pragma unroll
-              for (int x = 0; x < 16; ++x)
-                if (var_of(ck_rel, dist0, 8 * (x >> 2) + 4 * hh + (x & 3), 32 * jb + (lane & 31)) == var) s[x] = tt[x];
-            }
-          } else
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
             // K operands in two batches, so that only half of them are live at a time
@@ -279,6 +257,7 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
             const f32x4 lse4 = lse_q[2 * (x >> 2)];
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -lse4[x & 3]));
             if (need_mask && dj > 32 * ib + q0) p = 0.f;
+            if (MASKED && var_of(ck_rel, dist0, q0 + 4 * hh, 32 * jb + (lane & 31)) != rot) p = 0.f;  // another pass's pair
             colsum += p;
             const int src = ((t4 + q0) & 31) | (lane & 32);
             const float r = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, p)));
@@ -295,7 +274,17 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
             sp[0] += dneg;
             if ((lane & 31) != 0) sp[32] += dpos;
           }
-          col[jb] = colsum + __shfl_xor(colsum, 32);
+          col[jb] += colsum + __shfl_xor(colsum, 32);
+        }
+      }
+      };
+      if (!multi) {
+        blocks(std::false_type{}, 0);
+      } else {
+        for (int rot = 0; rot < 3; ++rot) {
+          if (!((need >> rot) & 1u)) continue;
+          if (q_var != rot) load_q(rot);
+          blocks(std::true_type{}, rot);
         }
       }
       if (PASS == 1) {
@@ -417,7 +406,8 @@ hipError_t launch_estimate(const vs_params& p, const void* q, const DcaArgs* dca
   const int64_t n_sc = (int64_t)p.n_q_heads * a.n_k;
   hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(n_sc / 1024 < 1 ? 1 : (n_sc / 1024 > 8192 ? 8192 : n_sc / 1024))),
                      dim3(256), 0, st, sscore, n_sc);
-  const int nw = pick_waves(a.group);
+  // the DCA instantiation needs more registers per wave: half as many heads per workgroup
+  const int nw = pick_waves(dca && a.group > 4 ? (a.group + 1) / 2 : a.group);
   const int hb = (int)ceil_div(a.group, nw);
 #define VS_EST_CASE(DD, WW) \
   if (p.head_dim == DD && nw == WW) return launch_est<DD, WW>(a, hb, st);
