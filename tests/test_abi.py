@@ -100,3 +100,66 @@ def test_null_misaligned_and_workspace_errors():
     assert L.vs_count_tiles(C.byref(p), ok, ok, ok, ok, None, ok, 1 << 30, None) == vs.VS_ERR_INVALID_ARG
     bad = _good().params(); bad.k_stride_tok = 60
     assert L.vs_dense_causal_prefill(C.byref(bad), ok, ok, ok, ok, None, ok, 1 << 30, None) == vs.VS_ERR_INVALID_ARG
+
+
+def test_dca_descriptor_is_checked_on_the_host():
+    L = vs.lib()
+    p = _good().params()
+    ok, odd = C.c_void_p(4096), C.c_void_p(4100)
+
+    def dca(q_succ=4096, q_inter=4096, chunk=128, window=64):
+        return vs.VsDca(q_succ, q_inter, chunk, window)
+
+    def dense(d):
+        return L.vs_dense_causal_prefill_dca(C.byref(p), ok, C.byref(d) if d is not None else None, ok, ok, ok, None,
+                                             None, 0, None)
+
+    assert dense(None) == vs.VS_ERR_INVALID_ARG
+    assert dense(dca(q_succ=None)) == vs.VS_ERR_INVALID_ARG
+    assert dense(dca(q_inter=4100)) == vs.VS_ERR_INVALID_ARG
+    assert dense(dca(chunk=0)) == vs.VS_ERR_INVALID_ARG
+    assert dense(dca(window=-64)) == vs.VS_ERR_INVALID_ARG
+    assert dense(dca(chunk=100)) == vs.VS_ERR_UNSUPPORTED
+    assert dense(dca(window=65)) == vs.VS_ERR_UNSUPPORTED
+    assert dense(dca()) == vs.VS_ERR_WORKSPACE          # the descriptor is fine: the next check is the workspace
+    d = dca(chunk=100)
+    assert L.vs_estimate_dca(C.byref(p), ok, C.byref(d), ok, ok, ok, None, ok, 1 << 30, None) == vs.VS_ERR_UNSUPPORTED
+    assert L.vs_sparse_attn_prefill_dca(C.byref(p), ok, C.byref(d), ok, ok, ok, ok, ok, ok, ok, None, ok, 1 << 30,
+                                        None) == vs.VS_ERR_UNSUPPORTED
+    assert L.vs_prefill_chunk_dca(C.byref(p), ok, C.byref(d), None, ok, ok, ok, None, ok, 1 << 30, None) == vs.VS_ERR_UNSUPPORTED
+    good, bad_sel = dca(), dca(window=65)
+    assert L.vs_prefill_chunk_dca(C.byref(p), ok, C.byref(good), C.byref(bad_sel), ok, ok, ok, None, ok, 1 << 30,
+                                  None) == vs.VS_ERR_UNSUPPORTED
+    assert L.vs_estimate_dca(C.byref(p), odd, C.byref(good), ok, ok, ok, None, ok, 1 << 30, None) == vs.VS_ERR_INVALID_ARG
+
+
+def test_options_and_the_workspaces_they_change():
+    ck = vs.Chunk(4, 1, 128, 64, 64 * 1024, 0.1, vertical_budget=8, slash_budget=70)   # one short chunk, long cache
+    try:
+        vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 1)
+        unsplit = vs.workspace_bytes(ck, vs.VS_WS_DENSE)
+        vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+        auto = vs.workspace_bytes(ck, vs.VS_WS_DENSE)
+        vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 2)
+        two = vs.workspace_bytes(ck, vs.VS_WS_DENSE)
+        # partial results: (D + 2) floats per row, head and range, each array rounded up to 256 bytes
+        assert two - unsplit == 2 * 4 * 64 * 128 * 4 + 2 * 4 * 64 * 2 * 4
+        assert auto - unsplit == 8 * (two - unsplit)          # 16 ranges chosen for 4 units
+        for bad in (-1, 17):
+            with pytest.raises(vs.VsError):
+                vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, bad)
+        with pytest.raises(vs.VsError):
+            vs.set_option(99, 0)
+    finally:
+        vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+    # a long chunk is never split
+    long_ck = vs.Chunk(28, 4, 128, 32768, 32768, 0.1, vertical_budget=8, slash_budget=70)
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 1)
+    a = vs.workspace_bytes(long_ck, vs.VS_WS_DENSE)
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+    assert vs.workspace_bytes(long_ck, vs.VS_WS_DENSE) == a
+    assert vs.workspace_bytes(long_ck, vs.VS_WS_SELECT) > 0
+    L = vs.lib()
+    ok = C.c_void_p(4096)
+    p = long_ck.params()
+    assert L.vs_select(C.byref(p), ok, ok, ok, ok, ok, ok, None, 0, None) == vs.VS_ERR_WORKSPACE

@@ -80,7 +80,7 @@ class Workload:
         return 1.0 / math.sqrt(self.head_dim)
 
 
-# The five BASELINE configurations.
+# The five benchmark configurations (tiny, dense 64K, 128K, 1M at the 7B shape, 1M at the 14B shape).
 WORKLOADS = {
     "tiny_4k": Workload("tiny_4k", 4, 1, 64, 4096, 1024, vertical_budget=128, slash_budget=256,
                         n_sink=16, config_id=0),
@@ -93,7 +93,7 @@ WORKLOADS = {
     "14b_1m": Workload("14b_1m", 40, 8, 128, 1048576, 32768, vertical_budget=2000,
                        slash_budget=8192, n_sink=512, n_sink_min=32, sink_mag_per_head=True,
                        heavy_tail=True, config_id=4),
-    # extra: the 7B configuration with planted, clustered slash lines (not a BASELINE configuration)
+    # extra: the 7B configuration with planted, clustered slash lines (not one of the five)
     "7b_1m_local": Workload("7b_1m_local", 28, 4, 128, 1048576, 32768, vertical_budget=1000,
                             slash_budget=6096, n_sink=256, sink_mag_per_head=True, local_mag=8.0, config_id=5),
     # extra: the 7B configuration with Dual Chunk Attention positions (chunks of 256K tokens, four of
