@@ -85,6 +85,7 @@ def main():
     ap.add_argument("--chunk-rows", type=int, default=0,
                     help="rows of the chunk (a multiple of 64) instead of the workload's 32768: short chunks at the end "
                          "of a long context, the decode-side use of the kernels")
+    ap.add_argument("--rounds-in-turn", type=int, default=0, help="VS_OPT_ATTN_ROUNDS_IN_TURN (1: no load balancing)")
     ap.add_argument("--key-split", type=int, default=0, help="VS_OPT_ATTN_KEY_SPLIT: 0 automatic, 1 never, n ranges")
     ap.add_argument("--layer-plan", choices=["equal", "dense", "sparse"], default="equal",
                     help="chunk boundaries of --layer: equal lengths, or vs_plan_chunks with that cost model")
@@ -116,6 +117,7 @@ def main():
     if args.chunk_rows:
         w = vsgen.scaled(w, chunk=args.chunk_rows)
     vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, args.key_split)
+    vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, args.rounds_in_turn)
     ci = args.chunk_index % w.n_chunks
     s = ci * w.chunk
     C = min(w.chunk, w.n_ctx - s)

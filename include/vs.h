@@ -250,8 +250,11 @@ int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model,
  *     kernel folds the partial results: 0 = automatic (up to 16 ranges, so that about 512
  *     workgroups run), 1 = never, 2..16 = that many ranges (at least 16 key blocks each).
  *     Results agree within the rounding of the fp32 partial sums.  Changes the workspace
- *     sizes like the option above. */
-enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0, VS_OPT_ATTN_KEY_SPLIT = 1 };
+ *     sizes like the option above.
+ *   VS_OPT_ATTN_ROUNDS_IN_TURN  0 (default): the rounds of the persistent attention launch are
+ *     dealt to its eight workgroup groups by weight (length of each head's block list), the
+ *     heaviest first to the least loaded group; 1: in turn.  Only the timing depends on it. */
+enum { VS_OPT_ATTN_SEGMENT_BLOCKS = 0, VS_OPT_ATTN_KEY_SPLIT = 1, VS_OPT_ATTN_ROUNDS_IN_TURN = 2 };
 int vs_set_option(int which, int64_t value);
 
 #ifdef __cplusplus

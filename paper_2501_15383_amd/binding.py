@@ -20,6 +20,7 @@ VS_ERR_INVALID_ARG, VS_ERR_UNSUPPORTED, VS_ERR_WORKSPACE, VS_ERR_HIP = -1, -2, -
 VS_WS_ESTIMATE, VS_WS_SELECT, VS_WS_SPARSE, VS_WS_DENSE, VS_WS_CHUNK, VS_WS_COUNT_TILES = range(6)
 VS_OPT_ATTN_SEGMENT_BLOCKS = 0
 VS_OPT_ATTN_KEY_SPLIT = 1
+VS_OPT_ATTN_ROUNDS_IN_TURN = 2
 
 
 class VsParams(C.Structure):

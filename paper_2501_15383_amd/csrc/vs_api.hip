@@ -164,6 +164,10 @@ int vs_set_option(int which, int64_t value) {
       if (value < 0 || value > (int64_t)INT32_MAX) return VS_ERR_INVALID_ARG;
       set_attn_segment_blocks((int)value);
       return VS_OK;
+    case VS_OPT_ATTN_ROUNDS_IN_TURN:
+      if (value != 0 && value != 1) return VS_ERR_INVALID_ARG;
+      set_attn_schedule_in_turn((int)value);
+      return VS_OK;
     case VS_OPT_ATTN_KEY_SPLIT:
       if (value < 0 || value > 16) return VS_ERR_INVALID_ARG;
       set_attn_key_split((int)value);

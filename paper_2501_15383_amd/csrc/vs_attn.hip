@@ -78,6 +78,10 @@ struct AttnArgs {
   // [s * sync_blocks, (s + 1) * sync_blocks) over all rounds so far
   int32_t sync_blocks, n_sync;
   uint32_t* arrive;
+  // sched[g][r]: the group-round that group g works on in its r-th round, -1 = none left
+  // (written by k_attn_schedule from the lengths of the heads' block lists; n_gr entries per group)
+  const int32_t* sched;
+  int32_t n_gr;
 };
 
 __device__ __forceinline__ bool bm_test(const uint32_t* bm, int i) {
@@ -163,8 +167,12 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
                          : n_full_gr + (a.n_rem * a.n_q_heads + a.members - 1) / a.members;
   uint32_t* const arr = a.arrive + (int64_t)grp * a.n_sync;
   const int s_glob_top = (int)((n_k - 1) / 64) / a.sync_blocks;  // highest sync segment of the chunk
-  for (int rnd = 0; rnd * 8 + grp < n_gr; ++rnd) {
-  const int gr = rnd * 8 + grp;
+  for (int rnd = 0; SPLIT ? rnd * 8 + grp < n_gr : rnd < n_gr; ++rnd) {
+  int gr = rnd * 8 + grp;
+  if constexpr (!SPLIT) {
+    gr = __builtin_amdgcn_readfirstlane(a.sched[grp * n_gr + rnd]);
+    if (gr < 0) break;
+  }
   int h, qt, sp = 0;
   if constexpr (SPLIT) {
     // unit u = ((head, tile), split), no pace keeping (the members walk different key ranges)
@@ -923,7 +931,7 @@ __global__ __launch_bounds__(256) void k_build_blocklist(const int32_t* s_idx, c
     __syncthreads();
   }
   for (int i = running + tid; i < ent_stride; i += 256) E[i] = kEntSentinel;
-  // The last word of the bitmap row (beyond every diagonal) tells the attention kernel how
+  // The last words of the bitmap row (beyond every diagonal): the last one tells the attention kernel how
   // sparse the list is: sync segments of this head are 2^shift times the base size, so that a
   // segment holds about as many listed key blocks as it would in a dense list.
   if (tid == 0) {
@@ -931,6 +939,7 @@ __global__ __launch_bounds__(256) void k_build_blocklist(const int32_t* s_idx, c
     int shift = 0;
     while (shift < 4 && ((uint32_t)n_blk >> (shift + 1)) >= n_ent) ++shift;
     A[n_words - 1] = (uint32_t)shift;
+    A[n_words - 2] = running;  // length of the list: the head's share of the work (k_attn_schedule)
   }
 }
 
@@ -999,9 +1008,14 @@ static int attn_sync_blocks(const vs_params& p) {
   while (sb * 2 * 3 * per_block <= (6 << 20)) sb *= 2;
   return sb;
 }
-size_t attn_sync_bytes(const vs_params& p) {
+static size_t attn_counter_bytes(const vs_params& p) {
   const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
   return align_up((size_t)8 * (size_t)ceil_div(n_blk, attn_sync_blocks(p)) * sizeof(uint32_t), 256);
+}
+size_t attn_sync_bytes(const vs_params& p) {
+  // counters, then the schedule: 8 rows of at most Hq x (query tiles) group-rounds
+  const size_t rounds = (size_t)p.n_q_heads * (size_t)ceil_div(p.q_len, (int64_t)64 * kAttnQBlocks);
+  return attn_counter_bytes(p) + align_up(8 * rounds * sizeof(int32_t), 256);
 }
 
 // Key split of short chunks.  With few (query tile, head) units the persistent launch would
@@ -1057,6 +1071,72 @@ __global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
   for (int e = 0; e < D / 64; ++e) op[64 * e + lane] = (__bf16)(acc[e] * inv);
   if (a.lse && lane == 0)
     a.lse[(int64_t)h * a.q_len + row] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
+}
+
+// Which group takes which group-round.  Heads differ in the length of their block lists (by a
+// factor of almost two in the 1M workloads), so dealing the rounds out in turn leaves some
+// groups idle at the end.  The rounds are weighed (list length x number of key blocks the
+// tiles can reach), sorted, and given one by one to the group with the least work so far; a
+// group works through its rounds in that (descending) order.  One workgroup; only the timing
+// of the attention launch depends on the result.
+constexpr int kSchedMax = 8192;  // rounds the sort is done for (beyond it: dealt out in turn)
+static int g_sched_in_turn = 0;
+void set_attn_schedule_in_turn(int on) { g_sched_in_turn = on ? 1 : 0; }
+__global__ __launch_bounds__(1024) void k_attn_schedule(const AttnArgs a, int32_t* sched, int in_turn) {
+  __shared__ float w[kSchedMax];
+  __shared__ uint16_t order[kSchedMax];
+  __shared__ float avg_ent;
+  const int tid = threadIdx.x, n_gr = a.n_gr;
+  if (n_gr > kSchedMax || in_turn) {
+    for (int x = tid; x < 8 * n_gr; x += 1024) {
+      const int g = x / n_gr, r = x - g * n_gr;
+      sched[x] = r * 8 + g < n_gr ? r * 8 + g : -1;
+    }
+    return;
+  }
+  if (tid == 0) {
+    double sum = 0;
+    for (int h = 0; h < a.n_q_heads; ++h) sum += (double)a.bm_a[(int64_t)h * a.bm_stride + a.bm_words - 2];
+    avg_ent = (float)(sum / a.n_q_heads);
+  }
+  __syncthreads();
+  const int n_full_gr = a.n_full * a.n_q_heads;
+  const int mb = (int)(a.q_start / 64);
+  for (int gr = tid; gr < n_gr; gr += 1024) {
+    float ent, reach;
+    if (gr < n_full_gr) {
+      const int h = gr % a.n_q_heads, c = a.n_full - 1 - gr / a.n_q_heads;
+      ent = (float)a.bm_a[(int64_t)h * a.bm_stride + a.bm_words - 2];
+      reach = (float)(mb + 2 * (a.n_rem + c * a.members + a.members / 2) + 2);  // key blocks before the chunk's middle tile
+    } else {
+      ent = avg_ent;  // leftover tiles of several heads
+      reach = (float)(mb + a.n_rem + 2);
+    }
+    w[gr] = ent * reach;
+  }
+  __syncthreads();
+  for (int gr = tid; gr < n_gr; gr += 1024) {
+    const float mine = w[gr];
+    int rank = 0;
+    for (int j = 0; j < n_gr; ++j) rank += (w[j] > mine || (w[j] == mine && j < gr)) ? 1 : 0;
+    order[rank] = (uint16_t)gr;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float load[8];
+    int cnt[8];
+    for (int g = 0; g < 8; ++g) { load[g] = 0.f; cnt[g] = 0; }
+    for (int i = 0; i < n_gr; ++i) {
+      int g = 0;
+      for (int x = 1; x < 8; ++x)
+        if (load[x] < load[g]) g = x;
+      const int gr = order[i];
+      sched[g * n_gr + cnt[g]++] = gr;
+      load[g] += w[gr];
+    }
+    for (int g = 0; g < 8; ++g)
+      for (int r = cnt[g]; r < n_gr; ++r) sched[g * n_gr + r] = -1;
+  }
 }
 
 __global__ __launch_bounds__(256) void k_fill_zero_u32(uint32_t* p, int64_t n) {
@@ -1119,6 +1199,10 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.sync_blocks = attn_sync_blocks(p);
   a.n_sync = (int)ceil_div(ceil_div(p.q_start + p.q_len, kBlock), a.sync_blocks);
   a.arrive = (uint32_t*)sync_ws;
+  a.n_gr = a.n_full * a.n_q_heads + (int)ceil_div((int64_t)a.n_rem * a.n_q_heads, a.members);
+  int32_t* const sched = (int32_t*)((char*)sync_ws + attn_counter_bytes(p));
+  a.sched = sched;
+  if (a.n_split == 1) hipLaunchKernelGGL(k_attn_schedule, dim3(1), dim3(1024), 0, st, a, sched, g_sched_in_turn);
   hipLaunchKernelGGL(k_fill_zero_u32, dim3((unsigned)ceil_div(8 * (int64_t)a.n_sync, 256)), dim3(256), 0, st,
                      a.arrive, 8 * (int64_t)a.n_sync);
   // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel

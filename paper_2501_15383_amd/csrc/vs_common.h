@@ -78,6 +78,7 @@ size_t attn_sync_bytes(const vs_params& p);
 // key split of short chunks: number of ranges (1 = none) and bytes of partial results
 int attn_split(const vs_params& p);
 void set_attn_key_split(int n);
+void set_attn_schedule_in_turn(int on);
 size_t attn_split_bytes(const vs_params& p);
 void set_attn_segment_blocks(int blocks);
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,

@@ -150,6 +150,10 @@ def test_options_and_the_workspaces_they_change():
                 vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, bad)
         with pytest.raises(vs.VsError):
             vs.set_option(99, 0)
+        with pytest.raises(vs.VsError):
+            vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, 2)
+        vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, 1)
+        vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, 0)
     finally:
         vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
     # a long chunk is never split

@@ -162,3 +162,27 @@ def test_sparse_cost_model_follows_counted_tiles():
     column_model = vs.chunk_cost(s, c, vs.VS_COST_SPARSE, nv, ns) - slash_model
     assert abs(tiles[:, 0].mean() - slash_model) <= 0.02 * slash_model, (tiles[:, 0].mean(), slash_model)
     assert (tiles[:, 1] <= column_model).all()
+
+
+@pytest.mark.parametrize("in_turn", [0, 1])
+def test_rounds_dealt_by_weight_or_in_turn_give_the_same_result(in_turn):
+    """Several rounds per group, heads with block lists of very different lengths: the order in which
+    the groups take the rounds only shapes the timing."""
+    rng = np.random.default_rng(310)
+    hq, hkv, d, c, s = 6, 1, 64, 2048, 4096      # 16 query tiles x 6 heads over 8 groups
+    n_k = s + c
+    q = rand_bf16(rng, (c, hq, d)); k = rand_bf16(rng, (n_k, hkv, d)); v = rand_bf16(rng, (n_k, hkv, d))
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d), vertical_budget=40, slash_budget=100)
+    sets = list(_rand_sets(rng, pb, 30, 30, force_cols=[0], force_offs=range(64)))
+    sets[3][1] = 70; sets[3][4] = 65                      # two heads with short lists
+    rows = np.sort(rng.choice(c, 48, replace=False))
+    ref_out, ref_lse = oracle.sparse_attention(pb, q, k, v, *sets, rows=rows)
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 1)
+    vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, in_turn)
+    try:
+        out, lse = vs.sparse_attn_prefill(chunk_of(pb), dev(q), dev(k), dev(v), *[_t(x) for x in sets], want_lse=True)
+        torch.cuda.synchronize()
+    finally:
+        vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, 0)
+    rt = torch.from_numpy(rows).cuda()
+    assert_attn_close(out[rt], lse[:, rt], ref_out, ref_lse, f"rounds in turn = {in_turn}")
