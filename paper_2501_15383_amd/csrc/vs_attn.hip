@@ -20,15 +20,20 @@
 //  * K/V tiles go from global memory straight into LDS (global_load_lds_dwordx4, no staging
 //    registers), double-buffered: the copy of tile t+1 runs under the MFMA work of tile t,
 //    one barrier per tile.  Rows are unpadded; 16-byte chunks are XOR-swizzled instead.
-//  * the exponentials of a tile use the running maximum of the previous tiles as reference
-//    (exact path kept for masked tiles, first tiles and an overflow guard), which takes the
-//    row maximum off the critical path; inside a tile the MFMAs of one 32-key half are
-//    interleaved by hand with the exponentials of the other half, operands two to four
-//    LDS reads ahead.
+//  * the exponentials use one fixed reference per row (the maximum of the row's first tile;
+//    an exact path with the true maximum is kept for masked tiles, first tiles and an
+//    overflow guard), so the steady state has no running-maximum update.  The V^T P^T product
+//    of a tile runs one step behind its K Q^T product, in one hand-interleaved instruction
+//    stream with the exponentials, operands three LDS reads ahead.
 //  * the tile walk reads a per-head list of (key block, query-block mask) entries through
 //    a 64-entry lane cache and lives entirely in scalar registers.
-//  * blockIdx -> (tile, head): the G heads that share a KV head and the same query tile run
-//    on one XCD back to back (shared L2), heaviest (latest) query tiles first.
+//  * persistent launch: two workgroups per compute unit in eight groups (one per XCD); a group
+//    works on consecutive query tiles of one head per round and keeps its members within a
+//    few sync segments of keys, so that K/V blocks are shared through the L2.  Which group
+//    takes which round is decided on the device from the lengths of the block lists.
+//  * template parameters: DCA (three rotations of the queries, chosen per (query, key)
+//    pattern; section 5.1) and SPLIT (short chunks: the key walk cut into ranges, partial
+//    results folded by k_attn_combine).  The plain kernel is its own instantiation.
 #include "vs_common.h"
 
 namespace vs {
