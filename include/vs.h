@@ -58,7 +58,9 @@ typedef struct vs_params {
   int32_t last_q;          /* W: estimation window, 1..64 (the paper uses the last 64
                               tokens of each chunk); effective W' = min(W, q_len)     */
   int64_t q_len;           /* C: rows of this chunk, >= 1                             */
-  int64_t q_start;         /* s: absolute position of row 0, multiple of `block`;
+  int64_t q_start;         /* s: absolute position of row 0, >= 0 (any value: the 64-key
+                              blocks of the mask are aligned to absolute positions;
+                              vs_chunk_cost alone wants a multiple of 64);
                               keys visible n_k = s + C (< 2^31)                       */
   int64_t q_stride_tok, q_stride_head;   /* Q  [C][Hq][D]     => (Hq*D, D)            */
   int64_t k_stride_tok, k_stride_head;   /* K  [>=n_k][Hkv][D] => (Hkv*D, D)          */

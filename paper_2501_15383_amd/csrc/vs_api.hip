@@ -30,7 +30,6 @@ int check_params(const vs_params* p, bool need_budgets) {
   if (p->head_dim != 64 && p->head_dim != 128) return VS_ERR_UNSUPPORTED;
   if (p->block != kBlock) return VS_ERR_UNSUPPORTED;
   if (p->last_q > 64) return VS_ERR_UNSUPPORTED;
-  if (p->q_start % kBlock != 0) return VS_ERR_UNSUPPORTED;
   const int d = p->head_dim;
   if (!stride_ok(p->q_stride_tok, p->q_stride_head, d) || !stride_ok(p->k_stride_tok, p->k_stride_head, d) ||
       !stride_ok(p->v_stride_tok, p->v_stride_head, d) || !stride_ok(p->o_stride_tok, p->o_stride_head, d))
@@ -96,7 +95,7 @@ const char* vs_status_string(int status) {
   switch (status) {
     case VS_OK: return "ok";
     case VS_ERR_INVALID_ARG: return "invalid argument (null pointer, shape, stride or alignment)";
-    case VS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128, block 64, last_q <= 64, q_start a multiple of 64)";
+    case VS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128, block 64, last_q <= 64; DCA chunk and window multiples of 64)";
     case VS_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case VS_ERR_HIP: return "HIP runtime error at launch";
     default: return "unknown status";

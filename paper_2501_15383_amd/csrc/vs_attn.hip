@@ -70,7 +70,12 @@ struct AttnArgs {
   int32_t v_budget;
   int32_t n_q_heads, n_kv_heads, group;
   int32_t n_qtiles;
+  // q_start is rounded down to a multiple of 64 and q_len grown by the same row_pad rows, so that
+  // query blocks stay aligned to absolute positions; the first row_pad rows of the launch are
+  // padding (nothing is loaded or stored for them).  q_rows is the caller's q_len.
   int64_t q_len, q_start;
+  int32_t row_pad;
+  int64_t q_rows;
   float scale_log2;  // softmax_scale * log2(e)
   // persistent launch: n_wg workgroups, workgroup b is member b / 8 of group b % 8 (the groups
   // follow the round-robin of workgroups over the 8 XCDs); in round r group g works on
@@ -255,7 +260,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       if (var == 1) qb = a.q_succ;
       if (var == 2) qb = a.q_inter;
     }
-    const int64_t rc = row < a.q_len ? row : a.q_len - 1;
+    int64_t rc = row - a.row_pad;  // the caller's row (clamped: padding and tail rows load a valid one)
+    rc = rc < 0 ? 0 : (rc < a.q_rows ? rc : a.q_rows - 1);
     const __bf16* qp = qb + rc * a.q_stride_tok + (int64_t)h * a.q_stride_head + 8 * hh;
 #pragma unroll
     for (int st = 0; st < DSTEPS; ++st) qreg[st] = *(const bf16x8*)(qp + 16 * st);
@@ -827,8 +833,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   if constexpr (SPLIT) {
     // this split's share of the row: accumulators and row sum relative to the reference m_o
-    if (row < a.q_len) {
-      const int64_t pr = ((int64_t)sp * a.n_q_heads + h) * a.q_len + row;
+    const int64_t ro = row - a.row_pad;
+    if (ro >= 0 && ro < a.q_rows) {
+      const int64_t pr = ((int64_t)sp * a.n_q_heads + h) * a.q_rows + ro;
       float* op = a.part_o + pr * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -845,8 +852,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       }
     }
   } else
-  if (row < a.q_len) {
-    __bf16* op = a.out + row * a.o_stride_tok + (int64_t)h * a.o_stride_head;
+  if (row >= a.row_pad && row < a.q_len) {
+    const int64_t ro = row - a.row_pad;
+    __bf16* op = a.out + ro * a.o_stride_tok + (int64_t)h * a.o_stride_head;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -857,7 +865,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
         *(bf16x4*)(op + 32 * db + 8 * vq + 4 * hh) = __builtin_convertvector(o4, bf16x4);
       }
     if (a.lse && hh == 0)
-      a.lse[(int64_t)h * a.q_len + row] =
+      a.lse[(int64_t)h * a.q_rows + ro] =
           l_tot > 0.f ? (m_o + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
   }
   enter_segment(-1, false);  // (a tile whose walk ended early has marked nothing yet)
@@ -1019,7 +1027,7 @@ static size_t attn_counter_bytes(const vs_params& p) {
 }
 size_t attn_sync_bytes(const vs_params& p) {
   // counters, then the schedule: 8 rows of at most Hq x (query tiles) group-rounds
-  const size_t rounds = (size_t)p.n_q_heads * (size_t)ceil_div(p.q_len, (int64_t)64 * kAttnQBlocks);
+  const size_t rounds = (size_t)p.n_q_heads * (size_t)ceil_div(p.q_len + p.q_start % kBlock, (int64_t)64 * kAttnQBlocks);
   return attn_counter_bytes(p) + align_up(8 * rounds * sizeof(int32_t), 256);
 }
 
@@ -1031,7 +1039,7 @@ static int g_key_split = 0;  // 0: automatic, 1: never, n: n ranges (still at le
 void set_attn_key_split(int n) { g_key_split = n < 0 ? 0 : (n > 16 ? 16 : n); }
 int attn_split(const vs_params& p) {
   if (g_key_split == 1) return 1;
-  const int64_t units = ceil_div(p.q_len, (int64_t)64 * kAttnQBlocks) * p.n_q_heads;
+  const int64_t units = ceil_div(p.q_len + p.q_start % kBlock, (int64_t)64 * kAttnQBlocks) * p.n_q_heads;
   const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
   int64_t s = g_key_split > 1 ? g_key_split : 512 / units;
   if (s > 16) s = 16;
@@ -1052,16 +1060,16 @@ __global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int h = blockIdx.y;
-  if (row >= a.q_len) return;
+  if (row >= a.q_rows) return;
   float M = -INFINITY;
   for (int sp = 0; sp < a.n_split; ++sp)
-    M = fmaxf(M, a.part_ml[2 * (((int64_t)sp * a.n_q_heads + h) * a.q_len + row)]);
+    M = fmaxf(M, a.part_ml[2 * (((int64_t)sp * a.n_q_heads + h) * a.q_rows + row)]);
   float L = 0.f, acc[D / 64];
 #pragma unroll
   for (int e = 0; e < D / 64; ++e) acc[e] = 0.f;
   if (M != -INFINITY) {
     for (int sp = 0; sp < a.n_split; ++sp) {
-      const int64_t pr = ((int64_t)sp * a.n_q_heads + h) * a.q_len + row;
+      const int64_t pr = ((int64_t)sp * a.n_q_heads + h) * a.q_rows + row;
       const float m = a.part_ml[2 * pr];
       if (m == -INFINITY) continue;
       const float w = __builtin_amdgcn_exp2f(m - M);
@@ -1075,7 +1083,7 @@ __global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < D / 64; ++e) op[64 * e + lane] = (__bf16)(acc[e] * inv);
   if (a.lse && lane == 0)
-    a.lse[(int64_t)h * a.q_len + row] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
+    a.lse[(int64_t)h * a.q_rows + row] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * kLn2 : -INFINITY;
 }
 
 // Which group takes which group-round.  Heads differ in the length of their block lists (by a
@@ -1173,8 +1181,11 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.v_idx = dense ? nullptr : v_idx; a.v_cnt = dense ? nullptr : v_cnt;
   a.v_budget = p.vertical_budget;
   a.n_q_heads = p.n_q_heads; a.n_kv_heads = p.n_kv_heads; a.group = p.n_q_heads / p.n_kv_heads;
-  a.n_qtiles = (int)ceil_div(p.q_len, 64 * NQB);
-  a.q_len = p.q_len; a.q_start = p.q_start;
+  a.row_pad = (int32_t)(p.q_start % kBlock);
+  a.q_start = p.q_start - a.row_pad;
+  a.q_len = p.q_len + a.row_pad;
+  a.q_rows = p.q_len;
+  a.n_qtiles = (int)ceil_div(a.q_len, 64 * NQB);
   a.scale_log2 = p.softmax_scale * kLog2e;
   // two workgroups fit a compute unit; one persistent workgroup per slot, in 8 groups
   static int n_cu = 0;
@@ -1245,7 +1256,7 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   }
 #undef VS_ATTN_LAUNCH
   if (split) {
-    const dim3 cgrid((unsigned)ceil_div(p.q_len, 4), (unsigned)p.n_q_heads);
+    const dim3 cgrid((unsigned)ceil_div(a.q_rows, 4), (unsigned)p.n_q_heads);
     if (p.head_dim == 128) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(k_attn_combine<64>, cgrid, dim3(256), 0, st, a);
   }
@@ -1255,7 +1266,8 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,
                               const BlockList& bl, int64_t* tiles, hipStream_t st) {
   hipLaunchKernelGGL(k_count_tiles, dim3(p.n_q_heads), dim3(256), 0, st, v_idx, v_cnt,
-                     p.vertical_budget, bl.bm_a, (int)bl.words, p.q_start, p.q_len, tiles);
+                     p.vertical_budget, bl.bm_a, (int)bl.words, p.q_start - p.q_start % kBlock,
+                     p.q_len + p.q_start % kBlock, tiles);
   return hipGetLastError();
 }
 

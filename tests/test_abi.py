@@ -63,7 +63,6 @@ def test_yarn_scale_helper():
     (dict(head_dim=96), vs.VS_ERR_UNSUPPORTED),
     (dict(block=32), vs.VS_ERR_UNSUPPORTED),
     (dict(last_q=65), vs.VS_ERR_UNSUPPORTED),
-    (dict(q_start=100), vs.VS_ERR_UNSUPPORTED),
     (dict(n_kv_heads=3), vs.VS_ERR_INVALID_ARG),
     (dict(q_len=0), vs.VS_ERR_INVALID_ARG),
     (dict(softmax_scale=0.0), vs.VS_ERR_INVALID_ARG),

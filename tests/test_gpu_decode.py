@@ -81,3 +81,47 @@ def test_key_split_is_run_to_run_identical_and_close_to_the_unsplit_kernel():
         vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
     assert (a.float() - p.float()).abs().max().item() <= 2e-2 and (la - lp).abs().max().item() < 1e-3
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,s,dca", [
+    (4, 1, 128, 1, 20000, None),        # a decode step at an arbitrary position
+    (4, 2, 64, 5, 777, None),
+    (2, 1, 128, 100, 1000, None),       # a chunk that starts and ends inside 64-key blocks
+    (7, 1, 128, 300, 8191, None),       # ... over several query tiles
+    (3, 1, 128, 64, 63, None),
+    (4, 2, 128, 130, 5000, (1024, 256)),  # with Dual Chunk Attention
+])
+def test_chunks_that_start_anywhere_match_the_oracle(hq, hkv, d, c, s, dca):
+    """q_start need not be a multiple of 64: the launch is padded back to the block boundary."""
+    rng = np.random.default_rng(1400 + c + s)
+    n_k = s + c
+    qs = [rand_bf16(rng, (c, hq, d)) for _ in range(3)]
+    k = rand_bf16(rng, (n_k, hkv, d)); v = rand_bf16(rng, (n_k, hkv, d))
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d), vertical_budget=60, slash_budget=100)
+    od = None if dca is None else oracle.Dca(dca[0], dca[1], qs[1], qs[2])
+    gd = None if dca is None else (dev(qs[1]), dev(qs[2]), dca[0], dca[1])
+    ck = chunk_of(pb)
+    # dense
+    ref_out, ref_lse = oracle.dense_attention(pb, qs[0], k, v, dca=od)
+    out, lse = vs.dense_causal_prefill(ck, dev(qs[0]), dev(k), dev(v), want_lse=True, dca=gd)
+    torch.cuda.synchronize()
+    assert_attn_close(out, lse, ref_out, ref_lse, f"dense C={c} s={s}")
+    # sparse on given sets
+    sets = _rand_sets(rng, pb, 50, 30, force_cols=[0], force_offs=range(64))
+    ref_out, ref_lse = oracle.sparse_attention(pb, qs[0], k, v, *sets, dca=od)
+    out, lse = vs.sparse_attn_prefill(ck, dev(qs[0]), dev(k), dev(v), *[_t(x) for x in sets], want_lse=True, dca=gd)
+    torch.cuda.synchronize()
+    assert_attn_close(out, lse, ref_out, ref_lse, f"sparse C={c} s={s}")
+    # estimate, and the whole chunk against its own stages
+    from gpu_util import f64
+    rvs, rss, _ = oracle.estimate(pb, qs[0], k, dca=od)
+    vsc, ssc, _ = vs.estimate(ck, dev(qs[0]), dev(k), dca=gd)
+    np.testing.assert_allclose(f64(vsc), rvs, rtol=2e-4, atol=1e-7)
+    np.testing.assert_allclose(f64(ssc), rss, rtol=2e-4, atol=1e-7)
+    sel = vs.select(ck, vsc, ssc)
+    a, _ = vs.sparse_attn_prefill(ck, dev(qs[0]), dev(k), dev(v), *sel, dca=gd)
+    b, _ = vs.prefill_chunk(ck, dev(qs[0]), dev(k), dev(v), dca=gd)
+    tiles = vs.count_tiles(ck, *sel)
+    torch.cuda.synchronize()
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert (tiles[:, 0] > 0).all()
