@@ -44,7 +44,7 @@ int check_ws(const void* ws, size_t have, size_t need) {
 }
 
 size_t sparse_ws_bytes(const vs_params& p, bool dense) {
-  return blocklist_bytes(p, dense) + attn_sync_bytes(p) + attn_split_bytes(p);
+  return blocklist_bytes(p, dense) + attn_sync_bytes(p) + attn_split_bytes(p, dense);
 }
 
 // layout of the VS_WS_CHUNK workspace

@@ -76,6 +76,11 @@ struct AttnArgs {
   int64_t q_len, q_start;
   int32_t row_pad;
   int64_t q_rows;
+  int64_t n_k;  // keys visible to the chunk
+  // Single-token dense decode with grouped queries: the G query heads of a KV group are the
+  // rows of one tile (so K and V are read once per group, not once per head); all rows then
+  // stand at the same position, pos_in_block keys into the diagonal block.
+  int32_t same_pos, pos_in_block;
   float scale_log2;  // softmax_scale * log2(e)
   // persistent launch: n_wg workgroups, workgroup b is member b / 8 of group b % 8 (the groups
   // follow the round-robin of workgroups over the 8 XCDs); in round r group g works on
@@ -163,7 +168,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int t = wv >> 1;                          // query block of this wave inside the tile
   const int il = ((wv & 1) << 5) + (lane & 31);   // row inside the query block
   const int hh = lane >> 5;
-  const int64_t n_k = a.q_start + a.q_len;
+  const int64_t n_k = a.n_k;
 
   // ---- persistent workgroup: one (query tile, head) per round ------------------------------
   // The `members` workgroups of a group take consecutive query tiles of ONE head, so they walk
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int m0 = (int)(a.q_start / 64) + qt * NQB;  // absolute index of query block t = 0
   const bool wave_valid = row0 + 64 * t + ((wv & 1) << 5) < a.q_len;
   const int64_t rows_in_tile = (a.q_len - row0) < 64 * NQB ? (a.q_len - row0) : 64 * NQB;
-  const int64_t last_pos = a.q_start + row0 + rows_in_tile - 1;
+  const int64_t last_pos = a.same_pos ? n_k - 1 : a.q_start + row0 + rows_in_tile - 1;
 
   const uint32_t* bmA = a.bm_a + (int64_t)h * a.bm_stride;
   const int seg_shift = __builtin_amdgcn_readfirstlane((int)bmA[a.bm_words - 1]);  // sparser list, longer sync segments
@@ -514,6 +519,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // K Q^T of a masked tile, of the first tile of a row block, or of a tile whose scores
   // outran the reference: true maximum first, then the exponentials.  Nothing may be pending
   // (the accumulators must be up to date when the reference moves).  Leaves the tile pending.
+  // offset of this row's position inside its 64-key block (the last key of the diagonal block it
+  // may use); packed decode: all rows stand at the same position
+  const int il_diag = a.same_pos ? a.pos_in_block : il;
   // DCA: first key block of the chunk that holds this wave's query block
   const int dca_cs = DCA ? ((m0 + t) / a.dca_cblk) * a.dca_cblk : 0;
   int need_var = 0;       // DCA: rotation this wave's tile needs; 3 = it differs inside the tile (codes in dcak_s)
@@ -544,7 +552,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
               const int code = (int)((cd >> (8 * x)) & 255u);
-              const int ev = code == 100 ? 0 : (il < code ? 1 : 2);
+              const int ev = code == 100 ? 0 : (il_diag < code ? 1 : 2);
               if (ev == var) {
                 if (jb == 0) s0[4 * xq + x] = tt[4 * xq + x];
                 else s1[4 * xq + x] = tt[4 * xq + x];
@@ -709,7 +717,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 #pragma unroll
       for (int x = 0; x < 16; ++x) {
         const int r = 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3);
-        if (r > il) sv[x] = -INFINITY;
+        if (r > il_diag) sv[x] = -INFINITY;
       }
     } else {
 #pragma unroll
@@ -1037,17 +1045,24 @@ size_t attn_sync_bytes(const vs_params& p) {
 // that workspace sizes do not depend on the device.
 static int g_key_split = 0;  // 0: automatic, 1: never, n: n ranges (still at least 16 key blocks each)
 void set_attn_key_split(int n) { g_key_split = n < 0 ? 0 : (n > 16 ? 16 : n); }
-int attn_split(const vs_params& p) {
+// dense attention of one token with grouped queries: the heads of a KV group share a tile
+bool attn_packed_decode(const vs_params& p, bool dense) {
+  return dense && p.q_len == 1 && p.n_q_heads > p.n_kv_heads && p.n_q_heads / p.n_kv_heads <= 64 * kAttnQBlocks;
+}
+int attn_split(const vs_params& p, bool dense) {
   if (g_key_split == 1) return 1;
-  const int64_t units = ceil_div(p.q_len + p.q_start % kBlock, (int64_t)64 * kAttnQBlocks) * p.n_q_heads;
+  const bool packed = attn_packed_decode(p, dense);
+  const int64_t units = packed ? p.n_kv_heads
+                               : ceil_div(p.q_len + p.q_start % kBlock, (int64_t)64 * kAttnQBlocks) * p.n_q_heads;
   const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
   int64_t s = g_key_split > 1 ? g_key_split : 512 / units;
-  if (s > 16) s = 16;
+  const int64_t cap = packed && g_key_split == 0 ? 128 : 16;  // few units when the heads are packed: more ranges
+  if (s > cap) s = cap;
   if (s > n_blk / 16) s = n_blk / 16;  // at least 16 key blocks per range
   return s < 2 ? 1 : (int)s;
 }
-size_t attn_split_bytes(const vs_params& p) {
-  const int s = attn_split(p);
+size_t attn_split_bytes(const vs_params& p, bool dense) {
+  const int s = attn_split(p, dense);
   if (s == 1) return 0;
   const size_t rows = (size_t)s * p.n_q_heads * (size_t)p.q_len;
   return align_up(rows * p.head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256);
@@ -1185,6 +1200,17 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.q_start = p.q_start - a.row_pad;
   a.q_len = p.q_len + a.row_pad;
   a.q_rows = p.q_len;
+  a.n_k = p.q_start + p.q_len;
+  a.same_pos = 0; a.pos_in_block = 0;
+  if (attn_packed_decode(p, dense)) {
+    // rows = the G heads of a KV group, "heads" = the KV heads: the strides say so
+    const int G = p.n_q_heads / p.n_kv_heads;
+    a.q_stride_tok = p.q_stride_head; a.q_stride_head = (int64_t)G * p.q_stride_head;
+    a.o_stride_tok = p.o_stride_head; a.o_stride_head = (int64_t)G * p.o_stride_head;
+    a.n_q_heads = p.n_kv_heads; a.group = 1;
+    a.same_pos = 1; a.pos_in_block = a.row_pad;
+    a.row_pad = 0; a.q_len = G; a.q_rows = G;   // lse [Hkv][G] is the caller's [Hq][1]
+  }
   a.n_qtiles = (int)ceil_div(a.q_len, 64 * NQB);
   a.scale_log2 = p.softmax_scale * kLog2e;
   // two workgroups fit a compute unit; one persistent workgroup per slot, in 8 groups
@@ -1198,11 +1224,11 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   }
   int members = (2 * n_cu) / 8;
   if (members < 1) members = 1;
-  a.n_split = attn_split(p);
+  a.n_split = attn_split(p, dense);
   a.part_o = a.part_ml = nullptr;
   if (a.n_split > 1) {
     if (!split_ws) return hipErrorInvalidValue;
-    const size_t rows = (size_t)a.n_split * p.n_q_heads * (size_t)p.q_len;
+    const size_t rows = (size_t)a.n_split * p.n_q_heads * (size_t)p.q_len;  // (packed decode: Hkv x G rows, the same)
     a.part_o = (float*)split_ws;
     a.part_ml = (float*)((char*)split_ws + align_up(rows * p.head_dim * sizeof(float), 256));
   }
@@ -1256,7 +1282,7 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   }
 #undef VS_ATTN_LAUNCH
   if (split) {
-    const dim3 cgrid((unsigned)ceil_div(a.q_rows, 4), (unsigned)p.n_q_heads);
+    const dim3 cgrid((unsigned)ceil_div(a.q_rows, 4), (unsigned)a.n_q_heads);
     if (p.head_dim == 128) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(k_attn_combine<64>, cgrid, dim3(256), 0, st, a);
   }

@@ -76,10 +76,10 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
                             hipStream_t st);
 size_t attn_sync_bytes(const vs_params& p);
 // key split of short chunks: number of ranges (1 = none) and bytes of partial results
-int attn_split(const vs_params& p);
+int attn_split(const vs_params& p, bool dense);
 void set_attn_key_split(int n);
 void set_attn_schedule_in_turn(int on);
-size_t attn_split_bytes(const vs_params& p);
+size_t attn_split_bytes(const vs_params& p, bool dense);
 void set_attn_segment_blocks(int blocks);
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,
                               const BlockList& bl, int64_t* tiles, hipStream_t st);

@@ -125,3 +125,30 @@ def test_chunks_that_start_anywhere_match_the_oracle(hq, hkv, d, c, s, dca):
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int16), b.view(torch.int16))
     assert (tiles[:, 0] > 0).all()
+
+
+@pytest.mark.parametrize("split", [0, 1, 7])
+@pytest.mark.parametrize("hq,hkv,d,s,dca", [
+    (28, 4, 128, 20000, None),       # the 7B shape: 7 query heads per KV head share a tile
+    (40, 8, 128, 4095, None),        # the 14B shape, last key of a block
+    (8, 2, 64, 4096, None),          # first key of a block
+    (6, 1, 128, 130, None),
+    (28, 4, 128, 9000, (2048, 512)), # with Dual Chunk Attention
+    (4, 4, 128, 5000, None),         # no grouping: the ordinary path
+])
+def test_single_token_dense_decode_matches_oracle(split, hq, hkv, d, s, dca):
+    """Dense attention of one token: the query heads of a KV group are packed into one tile."""
+    rng = np.random.default_rng(1500 + s)
+    qs = [rand_bf16(rng, (1, hq, d)) for _ in range(3)]
+    k = rand_bf16(rng, (s + 1, hkv, d)); v = rand_bf16(rng, (s + 1, hkv, d))
+    pb = oracle.Problem(hq, hkv, d, 1, s, 1.0 / np.sqrt(d))
+    od = None if dca is None else oracle.Dca(dca[0], dca[1], qs[1], qs[2])
+    gd = None if dca is None else (dev(qs[1]), dev(qs[2]), dca[0], dca[1])
+    ref_out, ref_lse = oracle.dense_attention(pb, qs[0], k, v, dca=od)
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, split)
+    try:
+        out, lse = vs.dense_causal_prefill(chunk_of(pb), dev(qs[0]), dev(k), dev(v), want_lse=True, dca=gd)
+        torch.cuda.synchronize()
+    finally:
+        vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+    assert_attn_close(out, lse, ref_out, ref_lse, f"decode {hq}/{hkv} s={s} split={split}")
