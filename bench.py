@@ -82,6 +82,8 @@ def main():
     ap.add_argument("--n-ctx", type=int, default=0, help="override the context length (tokens)")
     ap.add_argument("--segment-blocks", type=int, default=0,
                     help="64-key blocks per key segment of the sparse launch (0 = the library's choice)")
+    ap.add_argument("--local-mag", type=float, default=-1.0,
+                    help="override the strength of the planted slash structure of the workload (vsgen local_mag)")
     ap.add_argument("--chunk-rows", type=int, default=0,
                     help="rows of the chunk (a multiple of 64) instead of the workload's 32768: short chunks at the end "
                          "of a long context, the decode-side use of the kernels")
@@ -114,6 +116,8 @@ def main():
     w = vsgen.WORKLOADS[args.workload]
     if args.n_ctx:
         w = vsgen.scaled(w, n_ctx=args.n_ctx)
+    if args.local_mag >= 0:
+        w = vsgen.scaled(w, local_mag=args.local_mag)
     if args.chunk_rows:
         w = vsgen.scaled(w, chunk=args.chunk_rows)
     vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, args.key_split)
