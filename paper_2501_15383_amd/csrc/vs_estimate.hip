@@ -406,8 +406,9 @@ hipError_t launch_estimate(const vs_params& p, const void* q, const DcaArgs* dca
   const int64_t n_sc = (int64_t)p.n_q_heads * a.n_k;
   hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(n_sc / 1024 < 1 ? 1 : (n_sc / 1024 > 8192 ? 8192 : n_sc / 1024))),
                      dim3(256), 0, st, sscore, n_sc);
-  // the DCA instantiation needs more registers per wave: half as many heads per workgroup
-  const int nw = pick_waves(dca && a.group > 4 ? (a.group + 1) / 2 : a.group);
+  // large groups are split over two workgroups: two of them fit a compute unit, and the DCA
+  // instantiation needs the registers
+  const int nw = pick_waves(a.group > 4 ? (a.group + 1) / 2 : a.group);
   const int hb = (int)ceil_div(a.group, nw);
 #define VS_EST_CASE(DD, WW) \
   if (p.head_dim == DD && nw == WW) return launch_est<DD, WW>(a, hb, st);
