@@ -186,3 +186,38 @@ def test_rounds_dealt_by_weight_or_in_turn_give_the_same_result(in_turn):
         vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, 0)
     rt = torch.from_numpy(rows).cuda()
     assert_attn_close(out[rt], lse[:, rt], ref_out, ref_lse, f"rounds in turn = {in_turn}")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_scores_that_outrun_the_first_tiles_by_far(d):
+    """The walk starts at a row's own keys and goes backwards; its softmax reference is fixed by the
+    first tile.  Here earlier keys score 60 to 180 nats above everything seen before them, in three
+    steps, so the reference has to be raised (and the accumulators rescaled) several times per row;
+    a fourth group scores far below and must vanish."""
+    rng = np.random.default_rng(320 + d)
+    hq, hkv, c, s = 2, 1, 192, 2048
+    n_k = s + c
+    scale = 1.0 / np.sqrt(d)
+    qf = np.full((c, hq, d), 0.5, np.float32) + 0.01 * rng.standard_normal((c, hq, d)).astype(np.float32)
+    kf = 0.05 * rng.standard_normal((n_k, hkv, d)).astype(np.float32)
+    step = 60.0 / (scale * d * 0.5)                 # key value that adds 60 nats to the logit
+    kf[1280:1344] += step; kf[640:700] += 2 * step; kf[3:40] += 3 * step; kf[1500:1530] -= 3 * step
+    vf = rng.standard_normal((n_k, hkv, d)).astype(np.float32)
+    to_u16 = lambda x: (torch.from_numpy(x).bfloat16().view(torch.int16).numpy().view(np.uint16))
+    q, k, v = to_u16(qf), to_u16(kf), to_u16(vf)
+    pb = oracle.Problem(hq, hkv, d, c, s, scale, vertical_budget=48, slash_budget=n_k)
+    ref_out, ref_lse = oracle.dense_attention(pb, q, k, v)
+    assert ref_lse.min() > 150                     # the big keys dominate every row
+    out, lse = vs.dense_causal_prefill(chunk_of(pb), dev(q), dev(k), dev(v), want_lse=True)
+    torch.cuda.synchronize()
+    assert_attn_close(out, lse, ref_out, ref_lse, f"outrunning scores, dense, D={d}")
+    # sparse: every diagonal computed except those of the second group, which comes in as vertical columns
+    offs = np.array(sorted(set(range(n_k)) - set(range(s - 700, s + c - 640))), np.int32)
+    s_idx = np.full((hq, n_k), -1, np.int32); s_idx[:, :len(offs)] = offs
+    cols = np.array([0] + list(range(640, 680)), np.int32)
+    v_idx = np.full((hq, 48), -1, np.int32); v_idx[:, :len(cols)] = cols
+    sets = (v_idx, np.full(hq, len(cols), np.int32), s_idx, np.full(hq, len(offs), np.int32))
+    ref_out, ref_lse = oracle.sparse_attention(pb, q, k, v, *sets)
+    out, lse = vs.sparse_attn_prefill(chunk_of(pb), dev(q), dev(k), dev(v), *[_t(x) for x in sets], want_lse=True)
+    torch.cuda.synchronize()
+    assert_attn_close(out, lse, ref_out, ref_lse, f"outrunning scores, sparse, D={d}")
