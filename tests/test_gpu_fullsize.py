@@ -9,7 +9,7 @@ import torch
 import oracle
 import paper_2501_15383_amd as vs
 import vsgen
-from gpu_util import ATOL, RTOL, check_index_sets, chunk_of, f64
+from gpu_util import block_class_values, check_class_mass, check_index_sets, check_lse, check_rows, chunk_of, f64
 
 pytestmark = pytest.mark.gpu
 
@@ -22,12 +22,23 @@ def _sample_rows(rng, c, n):
 
 
 def _check_rows(out, lse, ref_out, ref_lse, heads, rows, what):
-    got = np.transpose(f64(out[rows][:, heads]), (1, 0, 2))
-    err = np.abs(got - ref_out)
-    bad = err > ATOL + RTOL * np.abs(ref_out)
-    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} sampled outputs off, max err {err.max():.4g}"
-    lg = f64(lse[heads][:, rows])
-    assert np.abs(lg - ref_lse).max() < 2e-3, f"{what}: lse max err {np.abs(lg - ref_lse).max():.4g}"
+    """Sampled rows: the element rule, the row-normalised rules and the tight lse rule."""
+    check_rows(np.transpose(f64(out[rows][:, heads]), (1, 0, 2)), ref_out, what)
+    check_lse(f64(lse[heads][:, rows]), ref_lse, what)
+
+
+def _check_block_classes(run, oracle_rows, n_k, w, heads, rows, what):
+    """Values that are 1 in dimension floor(j / 64) mod D: every output is the probability mass of
+    one class of key blocks, a sum of non-negative terms of the size of the output itself, so a
+    single dropped, doubled or misplaced 64-key tile shows (one tile is 1 / (tiles per class) of its
+    element: 1.7 % at 7,600 tiles per row, against a bound of 0.6 %)."""
+    Vc = block_class_values(n_k, w.n_kv_heads, w.head_dim)
+    oc = run(Vc)
+    torch.cuda.synchronize()
+    ref_c, _ = oracle_rows(vsgen.as_u16(Vc))
+    got = np.transpose(f64(oc[rows][:, heads]), (1, 0, 2))
+    np.testing.assert_allclose(ref_c.sum(-1), 1.0, rtol=1e-9)
+    check_class_mass(got, ref_c, what + ", block-class values")
 
 
 def _run_sparse_chunk(name, chunk_index, heads, n_rows, seed):
@@ -37,27 +48,31 @@ def _run_sparse_chunk(name, chunk_index, heads, n_rows, seed):
     C, n_k = w.chunk, s + w.chunk
     dev = torch.device("cuda:0")
     K, V = vsgen.make_kv(w, n_k, device=dev)
-    dca = odca = None   # workloads with Dual Chunk Attention positions: three rotations of the queries
+    dca = odca = sel = osel = None
     if w.dca_chunk > 0:
+        # Dual Chunk Attention positions: three rotations of the queries for the attention, and the
+        # selection's own (continuous relative positions, "Integrating with DCA")
         Q, q_succ, q_inter = vsgen.make_q_dca(w, s, s + C, device=dev)
         dca = (q_succ, q_inter, w.dca_chunk, w.dca_window)
         odca = oracle.Dca(w.dca_chunk, w.dca_window, vsgen.as_u16(q_succ), vsgen.as_u16(q_inter))
+        sel = vsgen.make_q_dca_select(w, s, s + C, device=dev)
+        osel = oracle.Dca(sel[2], sel[3], vsgen.as_u16(sel[0]), vsgen.as_u16(sel[1]))
     else:
         Q = vsgen.make_q(w, s, s + C, device=dev)
     pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, last_q=w.last_q,
                         vertical_budget=w.vertical_budget, slash_budget=w.slash_budget,
                         keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
     ck = chunk_of(pb)
-    vsc, ssc, lse_w = vs.estimate(ck, Q, K, want_lse=True, dca=dca)
+    vsc, ssc, lse_w = vs.estimate(ck, Q, K, want_lse=True, dca=sel)
     sets = vs.select(ck, vsc, ssc)
     out, lse = vs.sparse_attn_prefill(ck, Q, K, V, *sets, want_lse=True, dca=dca)
-    out2, _ = vs.prefill_chunk(ck, Q, K, V, dca=dca)
+    out2, _ = vs.prefill_chunk(ck, Q, K, V, dca=dca, dca_select=sel)
     torch.cuda.synchronize()
     assert torch.equal(out.view(torch.int16), out2.view(torch.int16)), "vs_prefill_chunk differs from its stages"
 
     qh, kh, vh = vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V)
     # ---- estimation and selection of the sampled heads against the oracle
-    rvs, rss, rlse = oracle.estimate(pb, qh, kh, heads=heads, dca=odca)
+    rvs, rss, rlse = oracle.estimate(pb, qh, kh, heads=heads, dca=osel)
     gv, gs = f64(vsc[heads]), f64(ssc[heads])
     np.testing.assert_allclose(f64(lse_w[heads]), rlse, atol=5e-4, rtol=0)
     np.testing.assert_allclose(gv.sum(1), min(w.last_q, C), rtol=2e-4)
@@ -78,6 +93,11 @@ def _run_sparse_chunk(name, chunk_index, heads, n_rows, seed):
     torch.cuda.synchronize()
     dev1 = (o1.float() - 1.0).abs().max().item()
     assert dev1 < 1e-2, f"{name}: rows of P do not sum to one ({dev1})"
+    del ones, o1
+    # ---- values that make every output a block-class mass
+    _check_block_classes(lambda Vc: vs.sparse_attn_prefill(ck, Q, K, Vc, *sets, dca=dca)[0],
+                         lambda vc: oracle.sparse_attention(pb, qh, kh, vc, *sets_h, heads=heads, rows=rows, dca=odca),
+                         n_k, w, heads, rows, f"{name} chunk {ci}")
     # ---- recall against the dense kernel on a slice of rows lies in (0, 1]
     tiles = vs.count_tiles(ck, *sets).cpu().numpy()
     assert (tiles[:, 0] > 0).all()
@@ -99,6 +119,9 @@ def test_dense_7b_64k_sampled_rows():
     rows = _sample_rows(np.random.default_rng(1), C, 20)
     ref_out, ref_lse = oracle.dense_attention(pb, vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V), heads=heads, rows=rows)
     _check_rows(out, lse, ref_out, ref_lse, heads, rows, "dense_7b_64k")
+    _check_block_classes(lambda Vc: vs.dense_causal_prefill(ck, Q, K, Vc)[0],
+                         lambda vc: oracle.dense_attention(pb, vsgen.as_u16(Q), vsgen.as_u16(K), vc, heads=heads, rows=rows),
+                         s + C, w, heads, rows, "dense_7b_64k")
     # the sparse entry point with every diagonal selected runs the same tiles: identical bits
     n_k = s + C
     ck2 = vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, vertical_budget=1, slash_budget=n_k)
@@ -140,3 +163,39 @@ def test_sparse_7b_1m_dca_chunks():
     # patterns; prefill chunk 8 starts a DCA chunk, so its rows cross the end of the local window
     _run_sparse_chunk("7b_1m_dca", -1, heads=[5, 22], n_rows=8, seed=6)
     _run_sparse_chunk("7b_1m_dca", 8, heads=[16], n_rows=8, seed=7)
+
+
+def test_determinism_at_headline_size():
+    """Run-to-run identical bytes at the sizes of configuration 3: the selection on 56 rows (28 heads x
+    {vertical, slash}) of 1,048,576 scores with heavy ties, and the whole chunk call on the last chunk
+    (every workgroup slot of the persistent attention launch busy, pace keeping active)."""
+    w = vsgen.WORKLOADS["7b_1m"]
+    dev = torch.device("cuda:0")
+    n_k, C = w.n_ctx, w.chunk
+    s = n_k - C
+    ck = vs.Chunk(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, last_q=w.last_q,
+                  vertical_budget=w.vertical_budget, slash_budget=w.slash_budget,
+                  keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
+    g = torch.Generator(device=dev).manual_seed(91)
+    # 37 distinct score values: thousands of ties at the threshold of every row
+    vsc = (torch.randint(0, 37, (w.n_q_heads, n_k), generator=g, device=dev).float() / 64.0).contiguous()
+    ssc = (torch.randint(0, 37, (w.n_q_heads, n_k), generator=g, device=dev).float() / 64.0).contiguous()
+    a = [x.clone() for x in vs.select(ck, vsc, ssc)]
+    b = vs.select(ck, vsc, ssc)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y), "vs_select differs between two runs"
+    # ties go to the lower index: two heads against the oracle's full sort
+    for h in (0, 27):
+        ref_v = oracle.select_one(f64(vsc[h]), w.vertical_budget, w.keep_first_cols)
+        ref_s = oracle.select_one(f64(ssc[h]), w.slash_budget, w.keep_local_band)
+        assert np.array_equal(a[0][h].cpu().numpy()[:len(ref_v)], ref_v) and int(a[1][h]) == len(ref_v)
+        assert np.array_equal(a[2][h].cpu().numpy()[:len(ref_s)], ref_s) and int(a[3][h]) == len(ref_s)
+    del vsc, ssc
+    K, V = vsgen.make_kv(w, n_k, device=dev)
+    Q = vsgen.make_q(w, s, n_k, device=dev)
+    o1, l1 = vs.prefill_chunk(ck, Q, K, V, want_lse=True)
+    o2, l2 = vs.prefill_chunk(ck, Q, K, V, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), "vs_prefill_chunk: out differs between two runs"
+    assert torch.equal(l1, l2), "vs_prefill_chunk: lse differs between two runs"
