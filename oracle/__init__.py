@@ -82,8 +82,6 @@ def lib() -> C.CDLL:
         _lib = C.CDLL(build())
         _lib.vso_yarn_softmax_scale.restype = C.c_double
         _lib.vso_yarn_softmax_scale.argtypes = [C.c_double, C.c_int]
-        _lib.vso_attention_recall.restype = C.c_double
-        _lib.vso_attention_recall.argtypes = [C.c_double, C.c_double]
     return _lib
 
 
@@ -106,6 +104,8 @@ def yarn_softmax_scale(s: float, head_dim: int) -> float:
 
 
 def attention_recall(lse_sparse, lse_full):
+    """Attention_Recall of every query: exp(softmax_lse_sparse - softmax_lse_full)
+    ("Sparsity refinement" paragraph), the definition written out."""
     return np.exp(np.asarray(lse_sparse, np.float64) - np.asarray(lse_full, np.float64))
 
 

@@ -389,11 +389,6 @@ int vso_attention_dca(const vso_params *p, const uint16_t *q_intra, const uint16
                         n_rows, rows, out, lse);
 }
 
-/* Attention_Recall = exp(lse_sparse - lse_full) ("Sparsity refinement" paragraph). */
-double vso_attention_recall(double lse_sparse, double lse_full) {
-  return exp(lse_sparse - lse_full);
-}
-
 /* Attention recall of one head over a chunk: the mean over the chunk's rows of
  * exp(lse_sparse - lse_full) ("Sparsity refinement" paragraph; the paper gives the
  * per-query quantity and compares it with a threshold per head -- the mean over the rows

@@ -115,3 +115,56 @@ def test_estimate_dca_matches_oracle(hq, hkv, d, c, s, w, chunk, window):
     np.testing.assert_allclose(f64(lse), rlse, atol=2e-4, rtol=0)
     np.testing.assert_allclose(f64(vsc), rvs, rtol=2e-4, atol=1e-7)
     np.testing.assert_allclose(f64(ssc), rss, rtol=2e-4, atol=1e-7)
+
+
+@pytest.mark.parametrize("hq,hkv,d,c,s,chunk,window,sel_chunk,sel_window", [
+    (4, 1, 64, 512, 1536, 512, 128, 512, 1024),    # the selection covers the whole chunk before the query's
+    (4, 2, 128, 384, 1408, 256, 64, 128, 0),       # different chunk lengths for the selection and the attention
+    (7, 1, 128, 200, 1848, 640, 192, 640, 1280),   # ragged chunk, GQA 7
+])
+def test_prefill_chunk_dca_selects_with_its_own_rotations(hq, hkv, d, c, s, chunk, window, sel_chunk, sel_window):
+    """Section 5.2, "Integrating with DCA": critical tokens are selected with other relative
+    positions than the attention uses.  The selection's rotations and the attention's are four
+    independent random tensors here (plus the shared intra-chunk one), so a call that estimated
+    with the attention's rotations, or attended with the selection's, cannot pass."""
+    from gpu_util import check_index_sets, f64
+    rng = np.random.default_rng(1100 + c)
+    n_k = s + c
+    q = rand_bf16(rng, (c, hq, d))
+    att = [rand_bf16(rng, (c, hq, d)) for _ in range(2)]
+    sel = [rand_bf16(rng, (c, hq, d)) for _ in range(2)]
+    k = rand_bf16(rng, (n_k, hkv, d)); v = rand_bf16(rng, (n_k, hkv, d))
+    bv, bs = 96, 200
+    pb = oracle.Problem(hq, hkv, d, c, s, 1.0 / np.sqrt(d), vertical_budget=bv, slash_budget=bs)
+    ck = chunk_of(pb)
+    qd, kd, vd = dev(q), dev(k), dev(v)
+    g_att = (dev(att[0]), dev(att[1]), chunk, window)
+    g_sel = (dev(sel[0]), dev(sel[1]), sel_chunk, sel_window)
+    out, lse = vs.prefill_chunk(ck, qd, kd, vd, want_lse=True, dca=g_att, dca_select=g_sel)
+    # the same three stages one by one: estimate with the selection's rotations, attend with DCA's
+    vsc, ssc, _ = vs.estimate(ck, qd, kd, dca=g_sel)
+    sets = vs.select(ck, vsc, ssc)
+    out2, lse2 = vs.sparse_attn_prefill(ck, qd, kd, vd, *sets, want_lse=True, dca=g_att)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16)) and torch.equal(lse, lse2)
+    # oracle: estimate with the selection's rotations ...
+    o_sel = oracle.Dca(sel_chunk, sel_window, sel[0], sel[1])
+    o_att = oracle.Dca(chunk, window, att[0], att[1])
+    rvs, rss, _ = oracle.estimate(pb, q, k, dca=o_sel)
+    np.testing.assert_allclose(f64(vsc), rvs, rtol=2e-4, atol=1e-7)
+    np.testing.assert_allclose(f64(ssc), rss, rtol=2e-4, atol=1e-7)
+    # ... which is not what the attention's rotations would have scored
+    wvs, _, _ = oracle.estimate(pb, q, k, dca=o_att)
+    assert np.abs(wvs - rvs).max() > 1e-3
+    sets_h = [x.cpu().numpy() for x in sets]
+    for h in range(hq):
+        check_index_sets(rvs[h], sets_h[0][h], sets_h[1][h], bv, 1, f"head {h} vertical")
+        check_index_sets(rss[h], sets_h[2][h], sets_h[3][h], bs, 64, f"head {h} slash")
+    # ... select, then attention with DCA's own rotations on the GPU's index sets
+    ref_out, ref_lse = oracle.sparse_attention(pb, q, k, v, *sets_h, dca=o_att)
+    assert_attn_close(out, lse, ref_out, ref_lse, f"chunk call with selection rotations C={c} s={s}")
+    # end to end from the oracle's own selection, wherever the two selections agree exactly
+    o_sets = oracle.select(pb, rvs, rss)
+    if all(np.array_equal(a, b) for a, b in zip(o_sets, sets_h)):
+        e2e_out, e2e_lse = oracle.sparse_attention(pb, q, k, v, *o_sets, dca=o_att)
+        assert_attn_close(out, lse, e2e_out, e2e_lse, "end to end")

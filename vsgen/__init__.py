@@ -29,7 +29,8 @@ rotated at j mod c; the queries come in three rotations, at i mod c (intra-chunk
 (i mod c) + c (successive-chunk: against a key of the chunk before, the difference is the true
 distance i - j) and at the constant c + dca_window - 1 (inter-chunk: no relative position
 exceeds what one chunk plus the window has seen).  Only the positions differ; which rotation
-meets which key is decided by the library and the oracle, not here.
+meets which key is decided by the library and the oracle, not here.  The selection of such a
+workload takes rotations of its own (make_q_dca_select: continuous relative positions).
 """
 from __future__ import annotations
 
@@ -250,6 +251,24 @@ def make_q_dca(w: Workload, t0: int, t1: int, device="cpu"):
     return (_make_q_at(w, t0, t1, i % w.dca_chunk, device),
             _make_q_at(w, t0, t1, i % w.dca_chunk + w.dca_chunk, device),
             _make_q_at(w, t0, t1, torch.full_like(i, w.dca_chunk + w.dca_window - 1), device))
+
+
+def make_q_dca_select(w: Workload, t0: int, t1: int, device="cpu"):
+    """The rotations the SELECTION of a Dual Chunk Attention workload uses for the successive-chunk
+    and the inter-chunk pattern, and the (chunk, window) that go with them: (q_succ, q_inter, c, 2c).
+    Section 5.2, "Integrating with DCA": the critical tokens are selected with relative positions
+    that stay continuous along a diagonal, the attention itself keeps DCA's own positions.  The
+    paper shows this in a figure that the text does not reproduce; this recipe's reading: for the
+    selection the successive-chunk pattern covers the whole chunk before the query's (window = 2c,
+    queries at (i mod c) + c, so the relative position is the true distance i - j up to 2c - 1), and
+    the inter-chunk pattern sits at the constant 2c - 1 where those distances end -- along a
+    diagonal the relative position is the true distance, then that constant, and never jumps back
+    as it does at the end of DCA's local window.  The intra-chunk rotation is shared with the attention."""
+    assert w.dca_chunk > 0
+    i = torch.arange(t0, t1, dtype=torch.int64, device=device)
+    c = w.dca_chunk
+    return (_make_q_at(w, t0, t1, i % c + c, device),
+            _make_q_at(w, t0, t1, torch.full_like(i, 2 * c - 1), device), c, 2 * c)
 
 
 def _make_kv_slab(w: Workload, t0: int, t1: int, device, sinks, mags, u):
