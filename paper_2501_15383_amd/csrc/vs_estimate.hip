@@ -44,6 +44,7 @@ struct EstArgs {
   int32_t n_q_heads, n_kv_heads, group;
   int32_t wp;        // W'
   int32_t n_ranges;
+  int32_t n_hb;      // workgroups per (key range, KV head): the heads of a group may be split
   int64_t q_len, n_k, p0;  // p0: position of window row 0
   float scale_log2;
 };
@@ -58,7 +59,15 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
   __shared__ float colbuf[PASS == 1 ? 2 * NH * 64 : 1];
   __shared__ __attribute__((aligned(16))) float lse_s[PASS == 1 ? NH * 64 : 4];
 
-  const int rng = blockIdx.x, g = blockIdx.y, hb = blockIdx.z;
+  // Workgroups b and b + 8 land on the same XCD (they are dealt to the 8 XCDs in turn) at about
+  // the same time.  The n_hb workgroups that share a (key range, KV head) unit are placed that
+  // way, so that the second one finds the unit's K rows in the L2 of that XCD:
+  //   b = 8 n_hb (unit / 8) + 8 hb + unit % 8
+  const int b_lin = blockIdx.x;
+  const int unit = (b_lin / (8 * a.n_hb)) * 8 + (b_lin & 7);
+  const int hb = (b_lin >> 3) % a.n_hb;
+  if (unit >= a.n_ranges * a.n_kv_heads) return;
+  const int rng = unit % a.n_ranges, g = unit / a.n_ranges;
   const int tid = threadIdx.x, lane = tid & 63, hh = lane >> 5;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int hw = wv >> 1, ib = wv & 1;  // head inside the workgroup, half of the window rows
@@ -371,8 +380,9 @@ size_t estimate_ws_bytes(const vs_params& p) {
 }
 
 template <int D, int NH>
-static hipError_t launch_est(const EstArgs& a, int hb, hipStream_t st) {
-  const dim3 grid(a.n_ranges, a.n_kv_heads, hb);
+static hipError_t launch_est(EstArgs a, int hb, hipStream_t st) {
+  a.n_hb = hb;
+  const dim3 grid((unsigned)(ceil_div((int64_t)a.n_ranges * a.n_kv_heads, 8) * 8 * hb));
   if (a.dca_chunk > 0) {
     hipLaunchKernelGGL((k_estimate<D, NH, 0, true>), grid, dim3(128 * NH), 0, st, a);
     hipLaunchKernelGGL(k_estimate_combine, dim3(a.n_q_heads), dim3(1024), 0, st, a);
@@ -407,7 +417,7 @@ hipError_t launch_estimate(const vs_params& p, const void* q, const DcaArgs* dca
   hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(n_sc / 1024 < 1 ? 1 : (n_sc / 1024 > 8192 ? 8192 : n_sc / 1024))),
                      dim3(256), 0, st, sscore, n_sc);
   // large groups are split over two workgroups: two of them fit a compute unit, and the DCA
-  // instantiation needs the registers
+  // instantiation needs the registers (the two are placed on one XCD, see the kernel)
   const int nw = pick_waves(a.group > 4 ? (a.group + 1) / 2 : a.group);
   const int hb = (int)ceil_div(a.group, nw);
 #define VS_EST_CASE(DD, WW) \
