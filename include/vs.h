@@ -128,14 +128,18 @@ int vs_sparse_attn_prefill(const vs_params *p, const void *q, const void *k,
                            const int32_t *s_cnt, void *out, float *lse, void *ws,
                            size_t ws_bytes, void *stream);
 
-/* Dense causal attention of the chunk (the paper's full attention, the thing the
- * sparse path is measured against): every key j <= p.  Same outputs as above;
- * lse is softmax_lse_full.  Budget fields of p are ignored. */
+/* Dense causal attention of the chunk: every key j <= p (section 5.2, "Sparsity
+ * refinement": the full attention whose softmax_lse_full the recall is measured
+ * against, `full_attention` in Algorithm 1; section 5.2 opening: the quadratic
+ * cost the sparse path avoids).  Same outputs as above; lse is softmax_lse_full.
+ * Budget fields of p are ignored. */
 int vs_dense_causal_prefill(const vs_params *p, const void *q, const void *k,
                             const void *v, void *out, float *lse, void *ws,
                             size_t ws_bytes, void *stream);
 
-/* One chunk of the whole path on one stream, no host synchronisation:
+/* One chunk of the whole path on one stream, no host synchronisation (section
+ * 5.2, "Integrating with Chunked prefill": every chunk selects its own critical
+ * tokens from its last 64 queries and then attends):
  * vs_estimate -> vs_select -> vs_sparse_attn_prefill.  Scores and index sets
  * live in the workspace (VS_WS_CHUNK). */
 int vs_prefill_chunk(const vs_params *p, const void *q, const void *k,
@@ -144,7 +148,9 @@ int vs_prefill_chunk(const vs_params *p, const void *q, const void *k,
 
 /* Work accounting for a set of index sets: per head, the number of 64x64
  * (query block, key block) tiles the sparse kernel issues for this chunk
- * (slash tiles, then vertical tiles of up to 64 gathered columns).
+ * (slash tiles, then vertical tiles of up to 64 gathered columns).  This is the
+ * unit in which the FLOPs "on computed blocks" are counted (section 5.3.1 quotes
+ * the kernel's FLOPs utilisation) and the cost that section 5.3.2 sizes chunks by.
  *   tiles: int64 [Hq][2] = {slash tiles, vertical tiles}. */
 int vs_count_tiles(const vs_params *p, const int32_t *v_idx, const int32_t *v_cnt,
                    const int32_t *s_idx, const int32_t *s_cnt, int64_t *tiles,
@@ -218,7 +224,43 @@ int vs_prefill_chunk_dca(const vs_params *p, const void *q_intra, const vs_dca *
                          const vs_dca *dca_select, const void *k, const void *v, void *out,
                          float *lse, void *ws, size_t ws_bytes, void *stream);
 
-/* Cost model and chunk planner (host functions; sec. 6.3 "Dynamic Chunked Pipeline
+/* Several requests in one launch (section 5.2, "Integrating with Chunked prefill": with
+ * chunked prefill, decoding of other requests is not held up behind a long prefill -- so
+ * an engine has, at any step, many short pieces of attention to run: single-token decode
+ * steps and short chunks of different requests against caches of different lengths).
+ * One call per request leaves most of the chip idle; this call packs the (request, head,
+ * query tile, key range) units of all requests into one persistent launch.
+ *
+ *   requests    DEVICE array [n_requests] of vs_request.  Every request has its own
+ *               q / out (bf16 [q_len][Hq][D]), cache k / v (bf16 [>= q_start + q_len][Hkv][D]),
+ *               optional lse (fp32 [Hq][q_len]), position and length; all share the head
+ *               counts, head_dim, strides, softmax scale and index-row lengths of p.
+ *               Index sets as for vs_sparse_attn_prefill (rows of p->vertical_budget /
+ *               p->slash_budget entries); all four index pointers null = dense causal
+ *               attention for that request.  Dense and sparse requests may be mixed.
+ *   p->q_len    the longest request of the batch (1 .. 4096)
+ *   p->q_start  such that p->q_start + p->q_len >= q_start + q_len of every request
+ *               (the most keys any request sees); the workspace is sized from these
+ *               two bounds, which is why they are host values while the requests
+ *               themselves stay on the device (no copy, no synchronisation).
+ * A request outside these bounds, or with a null q / k / v / out, is skipped on the
+ * device: its outputs are left untouched.  Results per request are those of
+ * vs_dense_causal_prefill / vs_sparse_attn_prefill up to the rounding of the fp32
+ * partial sums (the key walk of every unit may be cut into ranges, folded in a fixed
+ * order: run-to-run identical).  Workspace: vs_batch_workspace_bytes(p, n_requests).
+ * Returns VS_ERR_UNSUPPORTED for p->q_len > 4096 or n_requests > 4096. */
+typedef struct vs_request {
+  const void *q, *k, *v;
+  void *out;
+  float *lse;                                   /* may be null */
+  const int32_t *v_idx, *v_cnt, *s_idx, *s_cnt; /* all null: dense causal */
+  int64_t q_start, q_len;
+} vs_request;
+size_t vs_batch_workspace_bytes(const vs_params *p, int32_t n_requests);
+int vs_attn_batch(const vs_params *p, const vs_request *requests, int32_t n_requests,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/* Cost model and chunk planner (host functions; sec. 5.3.2 "Dynamic Chunked Pipeline
  * Parallelism": chunk sizes are adjusted to the complexity of the attention
  * kernel so that every chunk takes about the same time).  The unit is one 64x64
  * tile of one head.
@@ -238,8 +280,12 @@ double vs_chunk_cost(int64_t q_start, int64_t q_len, int32_t model,
 int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model,
                    int32_t vertical_budget, int32_t slash_budget, int64_t *bounds);
 
-/* Host: process-wide tuning switches (no device call; not thread-safe against
- * concurrent launches).  Returns VS_OK or VS_ERR_INVALID_ARG.
+/* Host: process-wide tuning switches (no device call).  Each switch is one atomic
+ * value, read by every later size query and launch of the process on any device;
+ * a size query and the call it is made for must see the same values, so do not
+ * change a switch between the two or while another thread is launching.  A call
+ * made under a setting that needs more workspace than it is given returns
+ * VS_ERR_WORKSPACE.  Returns VS_OK or VS_ERR_INVALID_ARG.
  *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per sync segment of the
  *     attention launches, 0 = automatic.  The attention kernels are persistent;
  *     workgroups that walk the same head keep within two sync segments of each

@@ -43,6 +43,13 @@ class VsDca(C.Structure):
     _fields_ = [("q_succ", C.c_void_p), ("q_inter", C.c_void_p), ("chunk", C.c_int64), ("window", C.c_int64)]
 
 
+class VsRequest(C.Structure):
+    """Mirror of `vs_request` in include/vs.h (11 eight-byte fields)."""
+    _fields_ = [("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p), ("out", C.c_void_p), ("lse", C.c_void_p),
+                ("v_idx", C.c_void_p), ("v_cnt", C.c_void_p), ("s_idx", C.c_void_p), ("s_cnt", C.c_void_p),
+                ("q_start", C.c_int64), ("q_len", C.c_int64)]
+
+
 class VsError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -92,6 +99,19 @@ def lib() -> C.CDLL:
         L.vs_set_option.argtypes = [C.c_int, C.c_int64]
         L.vs_count_tiles.restype = C.c_int
         L.vs_count_tiles.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_batch_workspace_bytes.restype = sz
+        L.vs_batch_workspace_bytes.argtypes = [P, C.c_int32]
+        L.vs_attn_batch.restype = C.c_int
+        L.vs_attn_batch.argtypes = [P, vp, C.c_int32, vp, sz, vp]
+        DP = C.POINTER(VsDca)
+        L.vs_estimate_dca.restype = C.c_int
+        L.vs_estimate_dca.argtypes = [P, vp, DP, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_sparse_attn_prefill_dca.restype = C.c_int
+        L.vs_sparse_attn_prefill_dca.argtypes = [P, vp, DP, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_dense_causal_prefill_dca.restype = C.c_int
+        L.vs_dense_causal_prefill_dca.argtypes = [P, vp, DP, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_prefill_chunk_dca.restype = C.c_int
+        L.vs_prefill_chunk_dca.argtypes = [P, vp, DP, DP, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -99,7 +119,8 @@ def lib() -> C.CDLL:
 EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
            "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step",
-           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca", "vs_estimate_dca", "vs_prefill_chunk_dca"]
+           "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca", "vs_estimate_dca", "vs_prefill_chunk_dca",
+           "vs_batch_workspace_bytes", "vs_attn_batch"]
 
 
 def status_string(status: int) -> str:
@@ -385,3 +406,31 @@ def count_tiles(ck: Chunk, v_idx, v_cnt, s_idx, s_cnt):
     _check(lib().vs_count_tiles(C.byref(p), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx), _ptr(s_cnt), _ptr(tiles),
                                 _ptr(ws), n, _stream()), "vs_count_tiles")
     return tiles
+
+
+def request_table(requests, device):
+    """The device array of vs_request for vs_attn_batch.  requests: dicts with q, k, v, out (bf16 tensors),
+    q_start, and optionally lse (fp32 [Hq][q_len]) and sets = (v_idx, v_cnt, s_idx, s_cnt) (absent: dense).
+    Returns an int64 tensor [n][11] (every field of vs_request is eight bytes); the tensors it points
+    to must stay alive until the call has run."""
+    rows = []
+    for r in requests:
+        sets = r.get("sets")
+        lse = r.get("lse")
+        rows.append([r["q"].data_ptr(), r["k"].data_ptr(), r["v"].data_ptr(), r["out"].data_ptr(),
+                     lse.data_ptr() if lse is not None else 0] +
+                    ([t.data_ptr() for t in sets] if sets is not None else [0, 0, 0, 0]) +
+                    [int(r["q_start"]), int(r["q"].shape[0])])
+    assert C.sizeof(VsRequest) == 88
+    return torch.tensor(rows, dtype=torch.int64).to(device)
+
+
+def attn_batch(ck: Chunk, table, n_requests, q, k, v, out, ws=None):
+    """vs_attn_batch.  ck: the shared shape with q_len = the longest request and q_start + q_len = the most
+    keys any request sees; table: from request_table; q / k / v / out: one request's tensors, for the strides."""
+    p = ck.params(q=q, k=k, v=v, out=out)
+    n = int(lib().vs_batch_workspace_bytes(C.byref(p), int(n_requests)))
+    if ws is None:
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device=table.device)
+    _check(lib().vs_attn_batch(C.byref(p), _ptr(table), int(n_requests), _ptr(ws), ws.numel(), _stream()), "vs_attn_batch")
+    return ws

@@ -345,6 +345,10 @@ int prefill_chunk_any(const vs_params* p, const void* q, const vs_dca* dca, cons
   if (rc != VS_OK) return rc;
   if (!q || !k || !v || !out) return VS_ERR_INVALID_ARG;
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
+  // both descriptors are checked before the first launch: a bad one must leave the stream untouched
+  DcaArgs scratch_da;
+  if (dca && (rc = check_dca(dca, &scratch_da)) != VS_OK) return rc;
+  if (sel && (rc = check_dca(sel, &scratch_da)) != VS_OK) return rc;
   const ChunkWs w = chunk_layout(*p);
   rc = check_ws(ws, ws_bytes, w.total);
   if (rc != VS_OK) return rc;
@@ -375,6 +379,31 @@ int vs_prefill_chunk_dca(const vs_params* p, const void* q_intra, const vs_dca* 
                          void* stream) {
   if (!dca) return VS_ERR_INVALID_ARG;
   return prefill_chunk_any(p, q_intra, dca, dca_select, k, v, out, lse, ws, ws_bytes, stream);
+}
+
+namespace {
+int check_batch(const vs_params* p, int32_t n_requests) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (n_requests < 1) return VS_ERR_INVALID_ARG;
+  if (p->q_len > 4096 || n_requests > 4096) return VS_ERR_UNSUPPORTED;
+  return VS_OK;
+}
+}  // namespace
+
+size_t vs_batch_workspace_bytes(const vs_params* p, int32_t n_requests) {
+  if (check_batch(p, n_requests) != VS_OK) return 0;
+  return attn_batch_bytes(*p, n_requests);
+}
+
+int vs_attn_batch(const vs_params* p, const vs_request* requests, int32_t n_requests, void* ws,
+                  size_t ws_bytes, void* stream) {
+  int rc = check_batch(p, n_requests);
+  if (rc != VS_OK) return rc;
+  if (!requests || !aligned(requests, 8)) return VS_ERR_INVALID_ARG;
+  rc = check_ws(ws, ws_bytes, attn_batch_bytes(*p, n_requests));
+  if (rc != VS_OK) return rc;
+  return hip_status(launch_attention_batch(*p, requests, n_requests, ws, (hipStream_t)stream));
 }
 
 int vs_count_tiles(const vs_params* p, const int32_t* v_idx, const int32_t* v_cnt,

@@ -34,9 +34,21 @@
 //  * template parameters: DCA (three rotations of the queries, chosen per (query, key)
 //    pattern; section 5.1) and SPLIT (short chunks: the key walk cut into ranges, partial
 //    results folded by k_attn_combine).  The plain kernel is its own instantiation.
+#include <atomic>
+#include <mutex>
+
 #include "vs_common.h"
 
 namespace vs {
+
+// a 64-bit value that is the same in every lane, moved into scalar registers
+template <typename T>
+__device__ __forceinline__ T uniform64(T x) {
+  static_assert(sizeof(T) == 8, "uniform64 takes pointers and 64-bit integers");
+  const uint64_t b = (uint64_t)x;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b), hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+  return (T)(((uint64_t)hi << 32) | lo);
+}
 
 struct AttnArgs {
   const __bf16* q;
@@ -97,7 +109,54 @@ struct AttnArgs {
   // (written by k_attn_schedule from the lengths of the heads' block lists; n_gr entries per group)
   const int32_t* sched;
   int32_t n_gr;
+  // Several requests in one launch (template parameter BATCH, always with SPLIT): a unit is
+  // (request, head, query tile, key range); the request's pointers, position and length come
+  // from req[r] and replace the fields above (batch_view).  n_qtiles is then the tile count of
+  // the longest request, bm_a / ent hold one list per (request, head), part_o / part_ml one
+  // region of n_split x Hq x rows_cap rows per request.  Requests beyond max_q_len / max_n_k
+  // (the bounds the workspace was sized for) are skipped.
+  const vs_request* req;
+  int32_t n_req, rows_cap, head_dim;
+  int64_t max_q_len, max_n_k;
 };
+
+// The arguments as request r of a batch sees them.  False: the request is outside the stated
+// bounds or has a null pointer, and is skipped (nothing of it is read or written).
+__device__ __forceinline__ bool batch_view(const AttnArgs& a0, int r, AttnArgs& a) {
+  vs_request rq = a0.req[r];   // the same address in every lane: the fields are uniform
+  rq.q = uniform64(rq.q); rq.k = uniform64(rq.k); rq.v = uniform64(rq.v); rq.out = uniform64(rq.out);
+  rq.lse = uniform64(rq.lse); rq.v_idx = uniform64(rq.v_idx); rq.v_cnt = uniform64(rq.v_cnt);
+  rq.s_idx = uniform64(rq.s_idx); rq.s_cnt = uniform64(rq.s_cnt);
+  rq.q_start = uniform64(rq.q_start); rq.q_len = uniform64(rq.q_len);
+  if (!rq.q || !rq.k || !rq.v || !rq.out) return false;
+  if (rq.q_len < 1 || rq.q_len > a0.max_q_len || rq.q_start < 0 || rq.q_start + rq.q_len > a0.max_n_k) return false;
+  const bool dense = rq.s_idx == nullptr;
+  if (!dense && (!rq.v_idx || !rq.v_cnt || !rq.s_cnt)) return false;
+  a.q = (const __bf16*)rq.q; a.k = (const __bf16*)rq.k; a.v = (const __bf16*)rq.v;
+  a.out = (__bf16*)rq.out; a.lse = rq.lse;
+  a.v_idx = dense ? nullptr : rq.v_idx;
+  a.v_cnt = dense ? nullptr : rq.v_cnt;
+  a.row_pad = (int32_t)(rq.q_start % kBlock);
+  a.q_start = rq.q_start - a.row_pad;
+  a.q_len = rq.q_len + a.row_pad;
+  a.q_rows = rq.q_len;
+  a.n_k = rq.q_start + rq.q_len;
+  a.bm_a = a0.bm_a + (int64_t)r * a0.n_q_heads * a0.bm_stride;
+  a.ent = a0.ent + (int64_t)r * a0.n_q_heads * a0.ent_stride;
+  const int64_t slot = (int64_t)r * a0.n_split * a0.n_q_heads * a0.rows_cap;
+  a.part_o = a0.part_o + slot * a0.head_dim;
+  a.part_ml = a0.part_ml + slot * 2;
+  if (dense && rq.q_len == 1 && a0.group > 1) {
+    // dense attention of one token: the G heads of a KV group are the rows of one tile
+    a.q_stride_tok = a0.q_stride_head; a.q_stride_head = (int64_t)a0.group * a0.q_stride_head;
+    a.o_stride_tok = a0.o_stride_head; a.o_stride_head = (int64_t)a0.group * a0.o_stride_head;
+    a.n_q_heads = a0.n_kv_heads; a.group = 1;
+    a.same_pos = 1; a.pos_in_block = a.row_pad;
+    a.row_pad = 0; a.q_len = a0.group; a.q_rows = a0.group;
+  }
+  a.n_qtiles = (int32_t)((a.q_len + 64 * kAttnQBlocks - 1) / (64 * kAttnQBlocks));
+  return true;
+}
 
 __device__ __forceinline__ bool bm_test(const uint32_t* bm, int i) {
   return (bm[i >> 5] >> (i & 31)) & 1u;
@@ -113,8 +172,13 @@ constexpr int attn_lds_bytes() { return 4 * 64 * D * 2 + 2 * 64 * 4 + 8 * 64; }
 // N such copies from one scalar base with per-copy lane offsets; the LDS destinations are
 // lds_addr, lds_addr + step, ...  (M0 is read when a copy issues, so it can move on at once;
 // a write to M0 needs one wait state before the copy that uses it.)
+// (lds_addr, sbase and step are the same in every lane; where the compiler cannot see that, the
+// values are moved into scalar registers here: the instructions take them from there)
 __device__ __forceinline__ void dma16x4(uint32_t lds_addr, const void* sbase, uint32_t o0, uint32_t o1,
                                         uint32_t o2, uint32_t o3, uint32_t step) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  step = __builtin_amdgcn_readfirstlane(step);
+  sbase = uniform64(sbase);
   asm volatile(
       "s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %5\n\t"
       "s_add_u32 m0, m0, %6\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %5\n\t"
@@ -124,12 +188,16 @@ __device__ __forceinline__ void dma16x4(uint32_t lds_addr, const void* sbase, ui
 }
 __device__ __forceinline__ void dma16x2(uint32_t lds_addr, const void* sbase, uint32_t o0, uint32_t o1,
                                         uint32_t step) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
+  step = __builtin_amdgcn_readfirstlane(step);
+  sbase = uniform64(sbase);
   asm volatile(
       "s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %3\n\t"
       "s_add_u32 m0, m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
       :: "s"(lds_addr), "v"(o0), "v"(o1), "s"(sbase), "s"(step) : "memory", "scc");
 }
 __device__ __forceinline__ void dma16_lane_ptr(uint32_t lds_addr, const void* ptr) {
+  lds_addr = __builtin_amdgcn_readfirstlane(lds_addr);
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                :: "s"(lds_addr), "v"(ptr) : "memory");
 }
@@ -137,8 +205,9 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)p;
 }
 
-template <int D, int NQB, bool DCA, bool SPLIT>
-__global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
+template <int D, int NQB, bool DCA, bool SPLIT, bool BATCH = false>
+__global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
+  static_assert(!BATCH || (SPLIT && !DCA), "several requests per launch ride on the key-split kernel");
   constexpr int DCH = D / 8;           // 16-byte chunks per row
   constexpr int DSTEPS = D / 16;       // MFMA k-steps of QK^T
   constexpr int DB = D / 32;           // 32-row blocks of O^T
@@ -168,7 +237,6 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   const int t = wv >> 1;                          // query block of this wave inside the tile
   const int il = ((wv & 1) << 5) + (lane & 31);   // row inside the query block
   const int hh = lane >> 5;
-  const int64_t n_k = a.n_k;
 
   // ---- persistent workgroup: one (query tile, head) per round ------------------------------
   // The `members` workgroups of a group take consecutive query tiles of ONE head, so they walk
@@ -177,18 +245,32 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
   // the XCD's L2, so that a K/V block is fetched from memory once per group and round.
   // Waiting is bounded and only shapes the timing: results never depend on it.
   const int grp = blockIdx.x & 7, member = blockIdx.x >> 3;
-  const int n_full_gr = a.n_full * a.n_q_heads;   // full rounds: latest chunks first, heads inside
-  const int n_gr = SPLIT ? (a.n_qtiles * a.n_split * a.n_q_heads + a.members - 1) / a.members
-                         : n_full_gr + (a.n_rem * a.n_q_heads + a.members - 1) / a.members;
-  uint32_t* const arr = a.arrive + (int64_t)grp * a.n_sync;
-  const int s_glob_top = (int)((n_k - 1) / 64) / a.sync_blocks;  // highest sync segment of the chunk
+  const int n_full_gr = a0.n_full * a0.n_q_heads;   // full rounds: latest chunks first, heads inside
+  const int n_gr = SPLIT ? (a0.n_qtiles * a0.n_split * a0.n_q_heads * (BATCH ? a0.n_req : 1) + a0.members - 1) / a0.members
+                         : n_full_gr + (a0.n_rem * a0.n_q_heads + a0.members - 1) / a0.members;
+  uint32_t* const arr = a0.arrive + (int64_t)grp * a0.n_sync;
+  const int s_glob_top = (int)((a0.n_k - 1) / 64) / a0.sync_blocks;  // highest sync segment of the chunk
   for (int rnd = 0; SPLIT ? rnd * 8 + grp < n_gr : rnd < n_gr; ++rnd) {
   int gr = rnd * 8 + grp;
   if constexpr (!SPLIT) {
-    gr = __builtin_amdgcn_readfirstlane(a.sched[grp * n_gr + rnd]);
+    gr = __builtin_amdgcn_readfirstlane(a0.sched[grp * n_gr + rnd]);
     if (gr < 0) break;
   }
+  AttnArgs a = a0;  // this round's view of the arguments (BATCH: those of the unit's request)
   int h, qt, sp = 0;
+  if constexpr (BATCH) {
+    const int per_head = a0.n_qtiles * a0.n_split, per_req = per_head * a0.n_q_heads;
+    const int u = gr * a0.members + member;
+    const int r = u / per_req;
+    if (r >= a0.n_req) continue;
+    int v = u - r * per_req;
+    h = v / per_head;
+    v -= h * per_head;
+    qt = v / a0.n_split;
+    sp = v - qt * a0.n_split;
+    if (!batch_view(a0, r, a)) continue;
+    if (h >= a.n_q_heads) continue;   // (heads packed into rows: only the KV heads have units)
+  } else
   if constexpr (SPLIT) {
     // unit u = ((head, tile), split), no pace keeping (the members walk different key ranges)
     const int per_head = a.n_qtiles * a.n_split;
@@ -207,6 +289,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     qt = h < a.n_q_heads ? a.n_rem - 1 - u % a.n_rem : a.n_qtiles;
     if (h >= a.n_q_heads) h = 0;
   }
+  const int64_t n_k = a.n_k;
   const int g = h / a.group;
   const uint32_t expected = (uint32_t)(rnd + 1) * (uint32_t)a.members;
   // marks key segments seg_done - 1, ..., s_new done for this member, then holds the workgroup
@@ -384,6 +467,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       const int64_t j0 = (int64_t)(m0 - (idx - (NQB - 1))) * 64;
       if (__builtin_expect(j0 + 64 <= n_k, 1)) {  // whole block in range: uniform bases + one per-lane 32-bit offset
         fast = true;
+#ifdef VS_X_NOCOPY
+        if (ei > ei0 + 1) return;
+#endif
         const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
         if constexpr (GPW == 4) dma16x4(kdst, kt, koff[0], koff[1], koff[2], koff[3], WAVES * 1024);
         else dma16x2(kdst, kt, koff[0], koff[1], WAVES * 1024);
@@ -405,6 +491,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
       const int64_t j0 = (int64_t)(m0 - (idx - (NQB - 1))) * 64;
       if (__builtin_expect(j0 + 64 <= n_k, 1)) {
         fast = true;
+#ifdef VS_X_NOCOPY
+        if (ei > ei0 + 1) return;
+#endif
         const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
         if constexpr (GPW == 4) dma16x4(vdst, vt, voff[0], voff[1], voff[2], voff[3], WAVES * 1024);
         else dma16x2(vdst, vt, voff[0], voff[1], WAVES * 1024);
@@ -646,7 +735,11 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     auto v_index = [&](int n) -> int { return n < NM + 3 * NBQ ? (n - NM) / 3 : n - NM - 2 * NBQ; };
     auto frag = [&](int n) -> bf16x8 {
       if (is_k(n)) return k_load(kb, k_index(n) / NM, k_index(n) % NM);
+#ifdef VS_X_NOVLDS
+      return qreg[v_index(n) % DSTEPS];
+#else
       return v_frag(vbp, v_index(n));
+#endif
     };
     bf16x8 fq[NB];
     f32x16 sa, sn;
@@ -810,7 +903,9 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
     int nn_kind = nxt_kind, nn_idx = nxt_idx, nn_mask = nxt_mask;
     if (nxt_kind != 2) advance(nn_kind, nn_idx, nn_mask);
     wait_copies();
+#ifndef VS_X_NOBARRIER
     __syncthreads();
+#endif
     cur_kind = nxt_kind; cur_idx = nxt_idx; cur_mask = nxt_mask;
     nxt_kind = nn_kind; nxt_idx = nn_idx; nxt_mask = nn_mask;
     buf ^= 1;
@@ -888,14 +983,29 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a) {
 // list then holds every cc for which A has a bit in [cc - (NQB-1), cc], with the per-query-
 // block mask, in ascending order, followed by sentinels up to the end of the row.
 // ---------------------------------------------------------------------------------------------
+// With req != null the launch builds one list per (request, head), blockIdx.x = r * n_heads + h:
+// offsets, their count, the number of key blocks and "dense" (no offsets given) come from the
+// request; a request outside the bounds the workspace was sized for gets no list (the attention
+// kernel skips it).
 template <int NQB>
 __global__ __launch_bounds__(256) void k_build_blocklist(const int32_t* s_idx, const int32_t* s_cnt,
                                                          int32_t s_budget, int dense, int n_blk,
                                                          int n_words, int ent_stride, uint32_t* bm_a,
-                                                         uint32_t* ent) {
-  const int h = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  uint32_t* A = bm_a + (int64_t)h * n_words;
-  uint32_t* E = ent + (int64_t)h * ent_stride;
+                                                         uint32_t* ent, const vs_request* req, int n_heads,
+                                                         int64_t max_q_len, int64_t max_n_k) {
+  int h = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  uint32_t* A = bm_a + (int64_t)blockIdx.x * n_words;
+  uint32_t* E = ent + (int64_t)blockIdx.x * ent_stride;
+  if (req) {
+    const vs_request rq = req[blockIdx.x / n_heads];
+    h = blockIdx.x % n_heads;
+    if (rq.q_len < 1 || rq.q_len > max_q_len || rq.q_start < 0 || rq.q_start + rq.q_len > max_n_k) return;
+    dense = rq.s_idx == nullptr;
+    if (!dense && !rq.s_cnt) return;
+    s_idx = rq.s_idx; s_cnt = rq.s_cnt;
+    n_blk = (int)((rq.q_start + rq.q_len + kBlock - 1) / kBlock);
+  }
   __shared__ uint32_t wsum[4];
   __shared__ uint32_t running;
   for (int w = tid; w < n_words; w += 256) {
@@ -1012,7 +1122,8 @@ hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, cons
   const int64_t n_k = p.q_start + p.q_len;
   const int n_blk = (int)ceil_div(n_k, kBlock);
   hipLaunchKernelGGL((k_build_blocklist<kAttnQBlocks>), dim3(bl.heads), dim3(256), 0, st, s_idx, s_cnt,
-                     p.slash_budget, dense ? 1 : 0, n_blk, (int)bl.words, (int)bl.ent_stride, bl.bm_a, bl.ent);
+                     p.slash_budget, dense ? 1 : 0, n_blk, (int)bl.words, (int)bl.ent_stride, bl.bm_a, bl.ent,
+                     (const vs_request*)nullptr, 1, (int64_t)0, (int64_t)0);
   return hipGetLastError();
 }
 
@@ -1020,10 +1131,14 @@ hipError_t launch_build_blocklist(const vs_params& p, const int32_t* s_idx, cons
 // (one XCD) may be at most two segments apart, so about three segments of K and V (64 KiB per
 // block at D = 128) are live in the caches at a time.  0 = automatic: 64 blocks at D = 128
 // (measured best for full lists; sparse lists scale it up per head, see k_build_blocklist).
-static int g_sync_blocks = 0;
-void set_attn_segment_blocks(int blocks) { g_sync_blocks = blocks < 0 ? 0 : blocks; }
+// (The tuning switches are process-wide atomics: a size query and the call it is for must see the
+// same values; a call under a setting that needs more workspace than it was given is refused by
+// the size check of the entry point.)
+static std::atomic<int> g_sync_blocks{0};
+void set_attn_segment_blocks(int blocks) { g_sync_blocks.store(blocks < 0 ? 0 : blocks, std::memory_order_relaxed); }
 static int attn_sync_blocks(const vs_params& p) {
-  if (g_sync_blocks > 0) return g_sync_blocks;
+  const int forced = g_sync_blocks.load(std::memory_order_relaxed);
+  if (forced > 0) return forced;
   const int per_block = kBlock * p.head_dim * 2 * 2;  // K and V of one KV head
   int sb = 1;
   while (sb * 2 * 3 * per_block <= (6 << 20)) sb *= 2;
@@ -1043,20 +1158,21 @@ size_t attn_sync_bytes(const vs_params& p) {
 // leave most of the chip idle, each unit walking the whole context alone; the walk is then cut
 // into n_split ranges.  The policy is fixed (512 workgroup slots: 256 compute units x 2), so
 // that workspace sizes do not depend on the device.
-static int g_key_split = 0;  // 0: automatic, 1: never, n: n ranges (still at least 16 key blocks each)
-void set_attn_key_split(int n) { g_key_split = n < 0 ? 0 : (n > 16 ? 16 : n); }
+static std::atomic<int> g_key_split{0};  // 0: automatic, 1: never, n: n ranges (still at least 16 key blocks each)
+void set_attn_key_split(int n) { g_key_split.store(n < 0 ? 0 : (n > 16 ? 16 : n), std::memory_order_relaxed); }
 // dense attention of one token with grouped queries: the heads of a KV group share a tile
 bool attn_packed_decode(const vs_params& p, bool dense) {
   return dense && p.q_len == 1 && p.n_q_heads > p.n_kv_heads && p.n_q_heads / p.n_kv_heads <= 64 * kAttnQBlocks;
 }
 int attn_split(const vs_params& p, bool dense) {
-  if (g_key_split == 1) return 1;
+  const int forced = g_key_split.load(std::memory_order_relaxed);
+  if (forced == 1) return 1;
   const bool packed = attn_packed_decode(p, dense);
   const int64_t units = packed ? p.n_kv_heads
                                : ceil_div(p.q_len + p.q_start % kBlock, (int64_t)64 * kAttnQBlocks) * p.n_q_heads;
   const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
-  int64_t s = g_key_split > 1 ? g_key_split : 512 / units;
-  const int64_t cap = packed && g_key_split == 0 ? 128 : 16;  // few units when the heads are packed: more ranges
+  int64_t s = forced > 1 ? forced : 512 / units;
+  const int64_t cap = packed && forced == 0 ? 128 : 16;  // few units when the heads are packed: more ranges
   if (s > cap) s = cap;
   if (s > n_blk / 16) s = n_blk / 16;  // at least 16 key blocks per range
   return s < 2 ? 1 : (int)s;
@@ -1070,11 +1186,16 @@ size_t attn_split_bytes(const vs_params& p, bool dense) {
 
 // out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), M = max_s m_s; one wave per (row, head),
 // splits folded in ascending order (fixed, so the result is run-to-run identical).
-template <int D>
-__global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
+template <int D, bool BATCH = false>
+__global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a0) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int h = blockIdx.y;
+  AttnArgs a = a0;
+  if constexpr (BATCH) {
+    if (!batch_view(a0, blockIdx.z, a)) return;
+    if (h >= a.n_q_heads) return;
+  }
   if (row >= a.q_rows) return;
   float M = -INFINITY;
   for (int sp = 0; sp < a.n_split; ++sp)
@@ -1108,8 +1229,8 @@ __global__ __launch_bounds__(256) void k_attn_combine(const AttnArgs a) {
 // group works through its rounds in that (descending) order.  One workgroup; only the timing
 // of the attention launch depends on the result.
 constexpr int kSchedMax = 8192;  // rounds the sort is done for (beyond it: dealt out in turn)
-static int g_sched_in_turn = 0;
-void set_attn_schedule_in_turn(int on) { g_sched_in_turn = on ? 1 : 0; }
+static std::atomic<int> g_sched_in_turn{0};
+void set_attn_schedule_in_turn(int on) { g_sched_in_turn.store(on ? 1 : 0, std::memory_order_relaxed); }
 __global__ __launch_bounds__(1024) void k_attn_schedule(const AttnArgs a, int32_t* sched, int in_turn) {
   __shared__ float w[kSchedMax];
   __shared__ uint16_t order[kSchedMax];
@@ -1171,6 +1292,45 @@ __global__ __launch_bounds__(256) void k_fill_zero_u32(uint32_t* p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0u;
 }
 
+// Per-device set-up, done once for each device a launch is made on (with that device current):
+// its number of compute units, and the opt-in of every attention instantiation to more than
+// 64 KiB of LDS per workgroup (a function attribute, held per device by the runtime).
+constexpr int kMaxDevices = 64;
+static hipError_t attn_device_setup(int* n_cu_out) {
+  static std::mutex mu;
+  static int cu_of[kMaxDevices] = {0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (cu_of[dev] == 0) {
+    constexpr int NQB = kAttnQBlocks;
+    int cu = 0;
+    e = hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    if (cu < 1) return hipErrorInvalidDevice;
+    const void* fns[10] = {reinterpret_cast<const void*>(&k_attention<128, NQB, false, false>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, false>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, true, false>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, true, false>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, false, true>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, true>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, true, true>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, true, true>),
+                          reinterpret_cast<const void*>(&k_attention<128, NQB, false, true, true>),
+                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, true, true>)};
+    for (int i = 0; i < 10; ++i) {
+      e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
+                              i % 2 == 0 ? attn_lds_bytes<128>() : attn_lds_bytes<64>());
+      if (e != hipSuccess) return e;
+    }
+    cu_of[dev] = cu;
+  }
+  *n_cu_out = cu_of[dev];
+  return hipSuccess;
+}
+
 hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dca, const void* k, const void* v,
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
                             const BlockList& bl, void* out, float* lse, void* sync_ws, void* split_ws,
@@ -1214,13 +1374,10 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.n_qtiles = (int)ceil_div(a.q_len, 64 * NQB);
   a.scale_log2 = p.softmax_scale * kLog2e;
   // two workgroups fit a compute unit; one persistent workgroup per slot, in 8 groups
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu < 1)
-      return hipErrorInvalidDevice;
-    n_cu = cu;
+  int n_cu = 0;
+  {
+    const hipError_t e = attn_device_setup(&n_cu);
+    if (e != hipSuccess) return e;
   }
   int members = (2 * n_cu) / 8;
   if (members < 1) members = 1;
@@ -1244,27 +1401,10 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.n_gr = a.n_full * a.n_q_heads + (int)ceil_div((int64_t)a.n_rem * a.n_q_heads, a.members);
   int32_t* const sched = (int32_t*)((char*)sync_ws + attn_counter_bytes(p));
   a.sched = sched;
-  if (a.n_split == 1) hipLaunchKernelGGL(k_attn_schedule, dim3(1), dim3(1024), 0, st, a, sched, g_sched_in_turn);
+  if (a.n_split == 1) hipLaunchKernelGGL(k_attn_schedule, dim3(1), dim3(1024), 0, st, a, sched,
+                                        g_sched_in_turn.load(std::memory_order_relaxed));
   hipLaunchKernelGGL(k_fill_zero_u32, dim3((unsigned)ceil_div(8 * (int64_t)a.n_sync, 256)), dim3(256), 0, st,
                      a.arrive, 8 * (int64_t)a.n_sync);
-  // more than 64 KiB of LDS per workgroup needs an explicit opt-in, once per kernel
-  static bool attr_set = false;
-  if (!attr_set) {
-    const void* fns[8] = {reinterpret_cast<const void*>(&k_attention<128, NQB, false, false>),
-                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, false>),
-                          reinterpret_cast<const void*>(&k_attention<128, NQB, true, false>),
-                          reinterpret_cast<const void*>(&k_attention<64, NQB, true, false>),
-                          reinterpret_cast<const void*>(&k_attention<128, NQB, false, true>),
-                          reinterpret_cast<const void*>(&k_attention<64, NQB, false, true>),
-                          reinterpret_cast<const void*>(&k_attention<128, NQB, true, true>),
-                          reinterpret_cast<const void*>(&k_attention<64, NQB, true, true>)};
-    for (int i = 0; i < 8; ++i) {
-      const hipError_t e = hipFuncSetAttribute(fns[i], hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               i % 2 == 0 ? attn_lds_bytes<128>() : attn_lds_bytes<64>());
-      if (e != hipSuccess) return e;
-    }
-    attr_set = true;
-  }
   const dim3 grid((unsigned)a.n_wg), block(128 * NQB);
   const bool split = a.n_split > 1;
 #define VS_ATTN_LAUNCH(DD, DCA_, SPLIT_) \
@@ -1285,6 +1425,89 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
     const dim3 cgrid((unsigned)ceil_div(a.q_rows, 4), (unsigned)a.n_q_heads);
     if (p.head_dim == 128) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(k_attn_combine<64>, cgrid, dim3(256), 0, st, a);
+  }
+  return hipGetLastError();
+}
+
+// ---- several requests per launch ----------------------------------------------------------------
+// p.q_len is the longest request, p.q_start + p.q_len the most keys any request sees.  The number
+// of key ranges is one for the whole batch, chosen so that about 512 workgroups have a unit.
+static int batch_rows_cap(const vs_params& p) {
+  const int G = p.n_q_heads / p.n_kv_heads;
+  return (int)(p.q_len > G ? p.q_len : G);   // a packed single-token request has G rows per KV head
+}
+static int batch_tiles(const vs_params& p) { return (int)ceil_div(p.q_len + kBlock - 1, (int64_t)64 * kAttnQBlocks); }
+int attn_batch_split(const vs_params& p, int n_req) {
+  const int64_t heads = p.q_len == 1 ? p.n_kv_heads : p.n_q_heads;   // single tokens: dense requests pack their heads
+  const int64_t units = (int64_t)n_req * heads * batch_tiles(p);
+  const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
+  int64_t s = 512 / units;
+  const int64_t cap = p.q_len == 1 ? 64 : 16;
+  if (s > cap) s = cap;
+  if (s > n_blk / 16) s = n_blk / 16;
+  return s < 1 ? 1 : (int)s;
+}
+size_t attn_batch_bytes(const vs_params& p, int n_req) {
+  const int64_t n_k = p.q_start + p.q_len;
+  const size_t lists = (size_t)n_req * p.n_q_heads;
+  const size_t rows = (size_t)n_req * attn_batch_split(p, n_req) * p.n_q_heads * (size_t)batch_rows_cap(p);
+  return align_up(lists * (size_t)bitmap_words(n_k) * 4, 256) + align_up(lists * (size_t)entry_stride(n_k) * 4, 256) +
+         align_up(rows * p.head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256) + 256;
+}
+
+hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int n_req, void* ws, hipStream_t st) {
+  constexpr int NQB = kAttnQBlocks;
+  const int64_t n_k = p.q_start + p.q_len;
+  const size_t lists = (size_t)n_req * p.n_q_heads;
+  const int64_t words = bitmap_words(n_k), ent_stride = entry_stride(n_k);
+  char* w = (char*)ws;
+  uint32_t* bm_a = (uint32_t*)w;
+  w += align_up(lists * (size_t)words * 4, 256);
+  uint32_t* ent = (uint32_t*)w;
+  w += align_up(lists * (size_t)ent_stride * 4, 256);
+  AttnArgs a = {};
+  a.n_split = attn_batch_split(p, n_req);
+  a.rows_cap = batch_rows_cap(p);
+  const size_t rows = (size_t)n_req * a.n_split * p.n_q_heads * (size_t)a.rows_cap;
+  a.part_o = (float*)w;
+  w += align_up(rows * p.head_dim * sizeof(float), 256);
+  a.part_ml = (float*)w;
+  w += align_up(rows * 2 * sizeof(float), 256);
+  a.arrive = (uint32_t*)w;   // unused by the key-split kernel; one valid word
+  a.n_sync = 1; a.sync_blocks = 1 << 30; a.sched = nullptr; a.n_gr = 0;
+  a.q_stride_tok = p.q_stride_tok; a.q_stride_head = p.q_stride_head;
+  a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
+  a.v_stride_tok = p.v_stride_tok; a.v_stride_head = p.v_stride_head;
+  a.o_stride_tok = p.o_stride_tok; a.o_stride_head = p.o_stride_head;
+  a.bm_a = bm_a; a.ent = ent;
+  a.bm_stride = words; a.bm_words = (int32_t)words;
+  a.ent_stride = ent_stride; a.ent_len = ent_stride;
+  a.v_budget = p.vertical_budget;
+  a.n_q_heads = p.n_q_heads; a.n_kv_heads = p.n_kv_heads; a.group = p.n_q_heads / p.n_kv_heads;
+  a.n_qtiles = batch_tiles(p);
+  a.n_k = n_k;
+  a.scale_log2 = p.softmax_scale * kLog2e;
+  a.req = req; a.n_req = n_req; a.head_dim = p.head_dim;
+  a.max_q_len = p.q_len; a.max_n_k = n_k;
+  int n_cu = 0;
+  hipError_t e = attn_device_setup(&n_cu);
+  if (e != hipSuccess) return e;
+  const int64_t units = (int64_t)n_req * a.n_q_heads * a.n_qtiles * a.n_split;
+  int members = (2 * n_cu) / 8;
+  if (members < 1) members = 1;
+  if (units < 8 * (int64_t)members) members = (int)ceil_div(units, 8);
+  a.members = members; a.n_wg = 8 * members; a.n_full = 0; a.n_rem = 0;
+  hipLaunchKernelGGL((k_build_blocklist<NQB>), dim3((unsigned)lists), dim3(256), 0, st, (const int32_t*)nullptr,
+                     (const int32_t*)nullptr, p.slash_budget, 0, 0, (int)words, (int)ent_stride, bm_a, ent, req,
+                     (int)p.n_q_heads, (int64_t)p.q_len, n_k);
+  const dim3 grid((unsigned)a.n_wg), block(128 * NQB);
+  const dim3 cgrid((unsigned)ceil_div(a.rows_cap, 4), (unsigned)a.n_q_heads, (unsigned)n_req);
+  if (p.head_dim == 128) {
+    hipLaunchKernelGGL((k_attention<128, NQB, false, true, true>), grid, block, attn_lds_bytes<128>(), st, a);
+    hipLaunchKernelGGL((k_attn_combine<128, true>), cgrid, dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL((k_attention<64, NQB, false, true, true>), grid, block, attn_lds_bytes<64>(), st, a);
+    hipLaunchKernelGGL((k_attn_combine<64, true>), cgrid, dim3(256), 0, st, a);
   }
   return hipGetLastError();
 }

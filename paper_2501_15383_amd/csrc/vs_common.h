@@ -74,6 +74,10 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
                             const int32_t* v_idx, const int32_t* v_cnt, bool dense,
                             const BlockList& bl, void* out, float* lse, void* sync_ws, void* split_ws,
                             hipStream_t st);
+// several requests in one launch (short chunks, decode steps): p.q_len = the longest request,
+// p.q_start + p.q_len = the most keys any request sees; req is a device array
+size_t attn_batch_bytes(const vs_params& p, int n_req);
+hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int n_req, void* ws, hipStream_t st);
 size_t attn_sync_bytes(const vs_params& p);
 // key split of short chunks: number of ranges (1 = none) and bytes of partial results
 int attn_split(const vs_params& p, bool dense);

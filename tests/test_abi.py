@@ -130,6 +130,31 @@ def test_dca_descriptor_is_checked_on_the_host():
     assert L.vs_prefill_chunk_dca(C.byref(p), ok, C.byref(good), C.byref(bad_sel), ok, ok, ok, None, ok, 1 << 30,
                                   None) == vs.VS_ERR_UNSUPPORTED
     assert L.vs_estimate_dca(C.byref(p), odd, C.byref(good), ok, ok, ok, None, ok, 1 << 30, None) == vs.VS_ERR_INVALID_ARG
+    # a bad attention descriptor is found before the estimate and the selection are enqueued, although
+    # the selection's own descriptor is fine (nothing may reach the stream when a status is negative)
+    bad_att = dca(chunk=100)
+    assert L.vs_prefill_chunk_dca(C.byref(p), ok, C.byref(bad_att), C.byref(good), ok, ok, ok, None, ok, 1 << 30,
+                                  None) == vs.VS_ERR_UNSUPPORTED
+    bad_att = dca(q_succ=None)
+    assert L.vs_prefill_chunk_dca(C.byref(p), ok, C.byref(bad_att), C.byref(good), ok, ok, ok, None, ok, 1 << 30,
+                                  None) == vs.VS_ERR_INVALID_ARG
+
+
+def test_dca_entry_points_have_prototypes():
+    """Every pointer and the size_t workspace size of the _dca calls go through declared argument types
+    (a workspace of 2 GiB or more would not survive ctypes' default int conversion)."""
+    L = vs.lib()
+    for name, n_args in (("vs_estimate_dca", 10), ("vs_sparse_attn_prefill_dca", 14),
+                         ("vs_dense_causal_prefill_dca", 10), ("vs_prefill_chunk_dca", 11)):
+        fn = getattr(L, name)
+        assert fn.argtypes is not None and len(fn.argtypes) == n_args, name
+        assert fn.argtypes[-2] is C.c_size_t and fn.restype is C.c_int, name
+        assert fn.argtypes[2] == C.POINTER(vs.VsDca), name
+    p = _good().params()
+    ok = C.c_void_p(4096)
+    d = vs.VsDca(4096, 4096, 128, 64)
+    # 3 GiB stated, but the pointer is null: the size must arrive whole for the check to say "workspace"
+    assert L.vs_dense_causal_prefill_dca(C.byref(p), ok, C.byref(d), ok, ok, ok, None, None, 3 << 30, None) == vs.VS_ERR_WORKSPACE
 
 
 def test_options_and_the_workspaces_they_change():
@@ -155,6 +180,15 @@ def test_options_and_the_workspaces_they_change():
         vs.set_option(vs.VS_OPT_ATTN_ROUNDS_IN_TURN, 0)
     finally:
         vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+    # the size query and the call must see the same options: a workspace sized under one setting is
+    # refused, on the host, by a call made under a setting that needs more
+    L = vs.lib()
+    ok = C.c_void_p(4096)
+    p = ck.params()
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 1)
+    small = vs.workspace_bytes(ck, vs.VS_WS_DENSE)
+    vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 0)
+    assert L.vs_dense_causal_prefill(C.byref(p), ok, ok, ok, ok, None, ok, small, None) == vs.VS_ERR_WORKSPACE
     # a long chunk is never split
     long_ck = vs.Chunk(28, 4, 128, 32768, 32768, 0.1, vertical_budget=8, slash_budget=70)
     vs.set_option(vs.VS_OPT_ATTN_KEY_SPLIT, 1)
@@ -166,3 +200,18 @@ def test_options_and_the_workspaces_they_change():
     ok = C.c_void_p(4096)
     p = long_ck.params()
     assert L.vs_select(C.byref(p), ok, ok, ok, ok, ok, ok, None, 0, None) == vs.VS_ERR_WORKSPACE
+
+
+def test_batch_argument_checks():
+    """vs_attn_batch: request table, counts, bounds and workspace are checked on the host."""
+    ck = vs.Chunk(4, 1, 64, 16, 0, 0.125, vertical_budget=8, slash_budget=70)
+    p = ck.params()
+    L = vs.lib()
+    ok = C.c_void_p(4096)
+    assert L.vs_attn_batch(C.byref(p), None, 2, ok, 1 << 30, None) == vs.VS_ERR_INVALID_ARG
+    assert L.vs_attn_batch(C.byref(p), ok, 0, ok, 1 << 30, None) == vs.VS_ERR_INVALID_ARG
+    assert L.vs_attn_batch(C.byref(p), ok, 5000, ok, 1 << 30, None) == vs.VS_ERR_UNSUPPORTED
+    assert L.vs_attn_batch(C.byref(p), ok, 2, ok, 16, None) == vs.VS_ERR_WORKSPACE
+    long = vs.Chunk(4, 1, 64, 5000, 0, 0.125, vertical_budget=8, slash_budget=70).params()
+    assert L.vs_attn_batch(C.byref(long), ok, 2, ok, 1 << 30, None) == vs.VS_ERR_UNSUPPORTED
+    assert L.vs_batch_workspace_bytes(C.byref(long), 2) == 0

@@ -1,4 +1,4 @@
-"""Host logic of the chunk planner (section 6.3: chunk sizes follow the complexity of the attention
+"""Host logic of the chunk planner (section 5.3.2: chunk sizes follow the complexity of the attention
 kernel so that every chunk takes about the same time) and its cost model."""
 import math
 
