@@ -45,7 +45,8 @@ enum {
   VS_ERR_INVALID_ARG = -1, /* null pointer, bad shape, bad stride, misalignment      */
   VS_ERR_UNSUPPORTED = -2, /* a valid request this build has no kernel for           */
   VS_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or too small             */
-  VS_ERR_HIP = -4          /* the HIP runtime refused a launch                       */
+  VS_ERR_HIP = -4,         /* the HIP runtime refused a launch                       */
+  VS_ERR_TOO_LARGE = -5    /* beyond the fixed capacity of an entry point that has one */
 };
 
 /* which workspace size vs_workspace_bytes() reports */
@@ -111,6 +112,21 @@ int vs_estimate(const vs_params *p, const void *q, const void *k, float *vscore,
 int vs_select(const vs_params *p, const float *vscore, const float *sscore,
               int32_t *v_idx, int32_t *v_cnt, int32_t *s_idx, int32_t *s_cnt,
               void *ws, size_t ws_bytes, void *stream);
+
+/* vs_select for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, outputs and results as vs_select, minus the workspace:
+ * the per-row control blocks (histograms, tickets, slice counts) live in a device
+ * array inside the library, 1.2 MB on every GPU the library runs on, for the life
+ * of the process.  The call allocates and frees nothing and clears what it uses
+ * with its own kernel.  Limits: n_q_heads <= 128 (VS_ERR_TOO_LARGE beyond, checked
+ * on the host before any device work).  All calls on one GPU share the array:
+ * calls that may overlap in time on one GPU (two streams, two threads) race --
+ * order them on one stream.  The first call on a device looks the array up
+ * (hipGetSymbolAddress); make that call outside graph capture. */
+int vs_select_static(const vs_params *p, const float *vscore, const float *sscore,
+                     int32_t *v_idx, int32_t *v_cnt, int32_t *s_idx, int32_t *s_cnt,
+                     void *stream);
 
 /* Step 3 (section 5.2: attention only on the selected critical tokens; section
  * 5.3.1: sparse K/V loading is what the kernel is tuned for).  The computed mask

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvs.so")
 
 VS_OK = 0
-VS_ERR_INVALID_ARG, VS_ERR_UNSUPPORTED, VS_ERR_WORKSPACE, VS_ERR_HIP = -1, -2, -3, -4
+VS_ERR_INVALID_ARG, VS_ERR_UNSUPPORTED, VS_ERR_WORKSPACE, VS_ERR_HIP, VS_ERR_TOO_LARGE = -1, -2, -3, -4, -5
 VS_WS_ESTIMATE, VS_WS_SELECT, VS_WS_SPARSE, VS_WS_DENSE, VS_WS_CHUNK, VS_WS_COUNT_TILES = range(6)
 VS_OPT_ATTN_SEGMENT_BLOCKS = 0
 VS_OPT_ATTN_KEY_SPLIT = 1
@@ -79,6 +79,8 @@ def lib() -> C.CDLL:
         L.vs_estimate.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_select.restype = C.c_int
         L.vs_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.vs_select_static.restype = C.c_int
+        L.vs_select_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp]
         L.vs_sparse_attn_prefill.restype = C.c_int
         L.vs_sparse_attn_prefill.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.vs_dense_causal_prefill.restype = C.c_int
@@ -116,7 +118,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select",
+EXPORTS = ["vs_workspace_bytes", "vs_status_string", "vs_yarn_softmax_scale", "vs_estimate", "vs_select", "vs_select_static",
            "vs_sparse_attn_prefill", "vs_dense_causal_prefill", "vs_prefill_chunk", "vs_count_tiles",
            "vs_set_option", "vs_chunk_cost", "vs_plan_chunks", "vs_select_heads", "vs_attention_recall", "vs_refine_step",
            "vs_sparse_attn_prefill_dca", "vs_dense_causal_prefill_dca", "vs_estimate_dca", "vs_prefill_chunk_dca",
@@ -259,6 +261,19 @@ def select(ck: Chunk, vscore, sscore, sets=None):
     p = ck.params()
     _check(lib().vs_select(C.byref(p), _ptr(vscore), _ptr(sscore), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx),
                            _ptr(s_cnt), _ptr(ws) if n else C.c_void_p(0), n, _stream()), "vs_select")
+    return v_idx, v_cnt, s_idx, s_cnt
+
+
+def select_static(ck: Chunk, vscore, sscore, sets):
+    """vs_select_static: vs_select with the library's own scratch array; `sets` (from alloc_index_sets) must be
+    passed in, nothing is allocated on the way."""
+    assert vscore.dtype == torch.float32 and vscore.is_contiguous() and vscore.shape == (ck.n_q_heads, ck.n_k)
+    assert sscore.dtype == torch.float32 and sscore.is_contiguous() and sscore.shape == (ck.n_q_heads, ck.n_k)
+    v_idx, v_cnt, s_idx, s_cnt = sets
+    _sets_ok(ck, v_idx, v_cnt, s_idx, s_cnt)
+    p = ck.params()
+    _check(lib().vs_select_static(C.byref(p), _ptr(vscore), _ptr(sscore), _ptr(v_idx), _ptr(v_cnt), _ptr(s_idx),
+                                  _ptr(s_cnt), _stream()), "vs_select_static")
     return v_idx, v_cnt, s_idx, s_cnt
 
 

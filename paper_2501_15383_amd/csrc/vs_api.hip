@@ -98,6 +98,7 @@ const char* vs_status_string(int status) {
     case VS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim must be 64 or 128, block 64, last_q <= 64; DCA chunk and window multiples of 64)";
     case VS_ERR_WORKSPACE: return "workspace missing, not 256-byte aligned, or too small";
     case VS_ERR_HIP: return "HIP runtime error at launch";
+    case VS_ERR_TOO_LARGE: return "request beyond the fixed capacity of this entry point (vs_select_static: at most 128 query heads)";
     default: return "unknown status";
   }
 }
@@ -220,6 +221,18 @@ int vs_select(const vs_params* p, const float* vscore, const float* sscore, int3
   rc = check_ws(ws, ws_bytes, select_ws_bytes(*p));
   if (rc != VS_OK) return rc;
   return hip_status(launch_select(*p, vscore, sscore, nullptr, nullptr, v_idx, v_cnt, s_idx, s_cnt, ws,
+                                  (hipStream_t)stream));
+}
+
+int vs_select_static(const vs_params* p, const float* vscore, const float* sscore, int32_t* v_idx,
+                     int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt, void* stream) {
+  int rc = check_params(p, true);
+  if (rc != VS_OK) return rc;
+  if (!vscore || !sscore || !v_idx || !v_cnt || !s_idx || !s_cnt) return VS_ERR_INVALID_ARG;
+  if (p->n_q_heads > select_static_max_heads()) return VS_ERR_TOO_LARGE;
+  void* scratch_ptr = nullptr;
+  if (select_static_scratch(&scratch_ptr) != hipSuccess) return VS_ERR_HIP;
+  return hip_status(launch_select(*p, vscore, sscore, nullptr, nullptr, v_idx, v_cnt, s_idx, s_cnt, scratch_ptr,
                                   (hipStream_t)stream));
 }
 

@@ -97,6 +97,10 @@ hipError_t launch_select(const vs_params& p, const float* vscore, const float* s
                          const int32_t* v_budget_h, const int32_t* s_budget_h,
                          int32_t* v_idx, int32_t* v_cnt, int32_t* s_idx, int32_t* s_cnt,
                          void* ws, hipStream_t st);
+// the selection's control blocks in a file-scope device array (callers that cannot allocate):
+// the most query heads it holds, and its address on the current device
+int select_static_max_heads();
+hipError_t select_static_scratch(void** ptr_out);
 hipError_t launch_recall(const vs_params& p, const float* lse_sparse, const float* lse_full, float* recall,
                          hipStream_t st);
 hipError_t launch_refine(const vs_params& p, const float* recall, float threshold, int32_t dv, int32_t ds,

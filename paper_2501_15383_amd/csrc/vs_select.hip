@@ -12,6 +12,8 @@
 //      keys == T (ties go to the lower index).  Ranks come from the slice counts, wave
 //      ballots and a 16-entry cross-wave scan (k_sel_write).
 // All of it is integer work, so the result is exact and run-to-run identical.
+#include <mutex>
+
 #include "vs_common.h"
 
 namespace vs {
@@ -288,6 +290,39 @@ hipError_t launch_select(const vs_params& p, const float* vscore, const float* s
   hipLaunchKernelGGL(k_sel_count, grid, dim3(kSelThreads), 0, st, a);
   hipLaunchKernelGGL(k_sel_write, grid, dim3(kSelThreads), 0, st, a);
   return hipGetLastError();
+}
+
+// ---- the selection for callers that cannot allocate ------------------------------------------
+// vs_select_static: the control blocks of the rows (histograms, tickets, slice counts) live in
+// a file-scope device array instead of a caller workspace.  Every device the library runs on
+// holds its own copy of the array (2 x 128 rows x 4,736 bytes = 1.2 MB) at its own address
+// until the process ends; in host code the array's name is only a handle, the address comes
+// from hipGetSymbolAddress, once per device, with that device current.  k_sel_init clears the
+// rows a call uses, so a call never sees the contents the call before it left behind; calls
+// that overlap in time on one device share the array and race.
+constexpr int kSelStaticMaxHeads = 128;
+static __device__ __align__(256) uint32_t scratch[2 * kSelStaticMaxHeads * kSelRowWords];
+
+int select_static_max_heads() { return kSelStaticMaxHeads; }
+
+hipError_t select_static_scratch(void** ptr_out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr_of[kMaxDevices] = {nullptr};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    ptr_of[dev] = ptr;
+  }
+  *ptr_out = ptr_of[dev];
+  return hipSuccess;
 }
 
 // ---- sparsity refinement ("Sparsity refinement" paragraph and Algorithm 1) --------------------

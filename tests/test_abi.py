@@ -42,7 +42,7 @@ def _good():
 
 
 def test_status_strings_and_workspace_sizes():
-    for st in (0, -1, -2, -3, -4, -99):
+    for st in (0, -1, -2, -3, -4, -5, -99):
         assert isinstance(vs.status_string(st), str) and vs.status_string(st)
     ck = _good()
     assert vs.workspace_bytes(ck, vs.VS_WS_ESTIMATE) > 0
@@ -200,6 +200,19 @@ def test_options_and_the_workspaces_they_change():
     ok = C.c_void_p(4096)
     p = long_ck.params()
     assert L.vs_select(C.byref(p), ok, ok, ok, ok, ok, ok, None, 0, None) == vs.VS_ERR_WORKSPACE
+
+
+def test_static_select_checks_its_capacity_on_the_host():
+    """vs_select_static holds 128 query heads; more is refused before any device work."""
+    L = vs.lib()
+    ok = C.c_void_p(4096)
+    big = vs.Chunk(160, 160, 64, 64, 0, 0.1, vertical_budget=4, slash_budget=70).params()
+    assert L.vs_select_static(C.byref(big), ok, ok, ok, ok, ok, ok, None) == vs.VS_ERR_TOO_LARGE
+    assert "128" in vs.status_string(vs.VS_ERR_TOO_LARGE)
+    p = _good().params()
+    assert L.vs_select_static(C.byref(p), None, ok, ok, ok, ok, ok, None) == vs.VS_ERR_INVALID_ARG
+    bad = _good(); bad.slash_budget = 0
+    assert L.vs_select_static(C.byref(bad.params()), ok, ok, ok, ok, ok, ok, None) == vs.VS_ERR_INVALID_ARG
 
 
 def test_batch_argument_checks():
