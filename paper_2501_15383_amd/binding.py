@@ -13,7 +13,8 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libvs.so")
+# VS_LIB_PATH names another build of the library (paper_2501_15383_amd.build --variant); there is still no fallback
+LIB_PATH = os.environ.get("VS_LIB_PATH") or os.path.join(_HERE, "libvs.so")
 
 VS_OK = 0
 VS_ERR_INVALID_ARG, VS_ERR_UNSUPPORTED, VS_ERR_WORKSPACE, VS_ERR_HIP, VS_ERR_TOO_LARGE = -1, -2, -3, -4, -5

@@ -37,13 +37,19 @@ def _stale(target: str, deps: list[str]) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False, extra_flags: list[str] | None = None) -> str:
-    os.makedirs(BUILD, exist_ok=True)
+def build(force: bool = False, verbose: bool = False, extra_flags: list[str] | None = None,
+          variant: str | None = None) -> str:
+    """Compile and link libvs.so.  With `variant` the objects go to _build/<variant>/ and the library
+    to libvs_<variant>.so next to libvs.so (a build with other -D switches, e.g. the timing diagnostics
+    of vs_attn.hip; load it by setting VS_LIB_PATH)."""
+    build_dir = os.path.join(BUILD, variant) if variant else BUILD
+    lib = os.path.join(HERE, f"libvs_{variant}.so") if variant else LIB
+    os.makedirs(build_dir, exist_ok=True)
     hipcc = _hipcc()
     flags = FLAGS + (extra_flags or [])
     jobs = []
     for s in SOURCES:
-        src, obj = os.path.join(CSRC, s), os.path.join(BUILD, s + ".o")
+        src, obj = os.path.join(CSRC, s), os.path.join(build_dir, s + ".o")
         if force or _stale(obj, [src] + HEADERS):
             jobs.append((src, obj))
 
@@ -61,14 +67,18 @@ def build(force: bool = False, verbose: bool = False, extra_flags: list[str] | N
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         list(ex.map(cc, jobs))
-    objs = [os.path.join(BUILD, s + ".o") for s in SOURCES]
-    if force or jobs or _stale(LIB, objs):
-        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    objs = [os.path.join(build_dir, s + ".o") for s in SOURCES]
+    if force or jobs or _stale(lib, objs):
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("link failed:\n" + r.stderr)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv, verbose=True))
+    # python -m paper_2501_15383_amd.build [--force] [--variant NAME -DSWITCH ...]
+    argv = sys.argv[1:]
+    var = argv[argv.index("--variant") + 1] if "--variant" in argv else None
+    print(build(force="--force" in argv, verbose=True, variant=var,
+                extra_flags=[a for a in argv if a.startswith("-D")]))

@@ -205,6 +205,14 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(size_t)(const __attribute__((address_space(3))) char*)p;
 }
 
+// Timing diagnostics (never defined in the library that ships; results are WRONG with any of them,
+// all accesses stay in bounds and every barrier that remains is reached by all waves):
+//   VS_X_NOVLDS     the V^T fragments of the fused step come from a register instead of LDS
+//                   (half of the LDS operand reads gone, same MFMA count)
+//   VS_X_NOCOPY     the global -> LDS copies of whole key blocks are skipped after the first two
+//   VS_X_NOBARRIER  no workgroup barrier at the end of a step
+// They split the time of a step into what the arithmetic stream, the operand reads, the copies
+// and the barrier cost.
 template <int D, int NQB, bool DCA, bool SPLIT, bool BATCH = false>
 __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
   static_assert(!BATCH || (SPLIT && !DCA), "several requests per launch ride on the key-split kernel");
