@@ -44,7 +44,10 @@ int check_ws(const void* ws, size_t have, size_t need) {
 }
 
 size_t sparse_ws_bytes(const vs_params& p, bool dense) {
-  return blocklist_bytes(p, dense) + attn_sync_bytes(p) + attn_split_bytes(p, dense);
+  const size_t own = blocklist_bytes(p, dense) + attn_sync_bytes(p) + attn_split_bytes(p, dense);
+  // (a sparse single-token call without DCA takes the packed path, a DCA one the plain path: room for either)
+  if (!dense && attn_single_token_packs(p)) return own > attn_single_token_bytes(p) ? own : attn_single_token_bytes(p);
+  return own;
 }
 
 // layout of the VS_WS_CHUNK workspace
@@ -294,8 +297,10 @@ int sparse_attn(const vs_params* p, const void* q, const vs_dca* dca, const void
   if (!aligned(q, 16) || !aligned(k, 16) || !aligned(v, 16) || !aligned(out, 16)) return VS_ERR_INVALID_ARG;
   rc = check_ws(ws, ws_bytes, sparse_ws_bytes(*p, false));
   if (rc != VS_OK) return rc;
-  const BlockList bl = blocklist_layout(*p, false, ws);
   hipStream_t st = (hipStream_t)stream;
+  if (!dca && attn_single_token_packs(*p))
+    return hip_status(launch_attention_single_token(*p, q, k, v, v_idx, v_cnt, s_idx, s_cnt, out, lse, ws, st));
+  const BlockList bl = blocklist_layout(*p, false, ws);
   hipError_t e = launch_build_blocklist(*p, s_idx, s_cnt, false, bl, st);
   if (e != hipSuccess) return VS_ERR_HIP;
   char* sync = (char*)ws + blocklist_bytes(*p, false);

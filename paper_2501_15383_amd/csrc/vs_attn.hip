@@ -118,7 +118,20 @@ struct AttnArgs {
   const vs_request* req;
   int32_t n_req, rows_cap, head_dim;
   int64_t max_q_len, max_n_k;
+  // Sparse attention of ONE token with grouped queries (BATCH only; set per request by batch_view):
+  // the G <= 16 heads of a KV group are the rows of one tile, as in the dense case, so K and V are
+  // read once per group.  The tile walks the UNION of the heads' block lists (ent_u, one list per
+  // (request, KV head), entries ((diagonal + 1) << 4) | 1); ent_hm holds, per entry, the heads
+  // whose own list has that diagonal (bit j = head j of the group): a row takes part in a tile
+  // iff its bit is set.  The gathered columns then follow head by head (every head has its own
+  // column set; only that head's row is live in its tiles).
+  const uint32_t* ent_u;
+  const uint32_t* ent_hm;
+  uint32_t* bm_u;          // union bitmaps [n_req][Hkv][words] (scratch of the list builder)
+  const uint32_t* hm;      // this request's masks (set by batch_view)
+  int32_t packed_sparse, group_rows;
 };
+constexpr int kPackedSparseMaxGroup = 16;
 
 // The arguments as request r of a batch sees them.  False: the request is outside the stated
 // bounds or has a null pointer, and is skipped (nothing of it is read or written).
@@ -146,13 +159,23 @@ __device__ __forceinline__ bool batch_view(const AttnArgs& a0, int r, AttnArgs& 
   const int64_t slot = (int64_t)r * a0.n_split * a0.n_q_heads * a0.rows_cap;
   a.part_o = a0.part_o + slot * a0.head_dim;
   a.part_ml = a0.part_ml + slot * 2;
-  if (dense && rq.q_len == 1 && a0.group > 1) {
-    // dense attention of one token: the G heads of a KV group are the rows of one tile
+  a.packed_sparse = 0;
+  a.group_rows = a0.group;
+  const bool pack_sparse = !dense && a0.ent_u && a0.group <= kPackedSparseMaxGroup;
+  if (rq.q_len == 1 && a0.group > 1 && (dense || pack_sparse)) {
+    // attention of one token: the G heads of a KV group are the rows of one tile
+    if (!dense) {
+      a.packed_sparse = 1;
+      a.v_idx = rq.v_idx; a.v_cnt = rq.v_cnt;   // indexed by the heads of the unit's group
+      a.ent = a0.ent_u + (int64_t)r * a0.n_kv_heads * a0.ent_stride;
+      a.hm = a0.ent_hm + (int64_t)r * a0.n_kv_heads * a0.ent_stride;
+    }
     a.q_stride_tok = a0.q_stride_head; a.q_stride_head = (int64_t)a0.group * a0.q_stride_head;
     a.o_stride_tok = a0.o_stride_head; a.o_stride_head = (int64_t)a0.group * a0.o_stride_head;
     a.n_q_heads = a0.n_kv_heads; a.group = 1;
     a.same_pos = 1; a.pos_in_block = a.row_pad;
     a.row_pad = 0; a.q_len = a0.group; a.q_rows = a0.group;
+    a.n_split = a0.n_split * a0.group;   // see the unit decode of k_attention
   }
   a.n_qtiles = (int32_t)((a.q_len + 64 * kAttnQBlocks - 1) / (64 * kAttnQBlocks));
   return true;
@@ -277,7 +300,13 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     qt = v / a0.n_split;
     sp = v - qt * a0.n_split;
     if (!batch_view(a0, r, a)) continue;
-    if (h >= a.n_q_heads) continue;   // (heads packed into rows: only the KV heads have units)
+    if (a.same_pos) {
+      // heads packed into rows: the unit slots of the G heads of a group become G times as many key
+      // ranges of the group's one tile
+      sp += (h % a0.group) * a0.n_split;
+      h /= a0.group;
+    }
+    if (h >= a.n_q_heads) continue;
   } else
   if constexpr (SPLIT) {
     // unit u = ((head, tile), split), no pace keeping (the members walk different key ranges)
@@ -333,12 +362,19 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
   const int64_t rows_in_tile = (a.q_len - row0) < 64 * NQB ? (a.q_len - row0) : 64 * NQB;
   const int64_t last_pos = a.same_pos ? n_k - 1 : a.q_start + row0 + rows_in_tile - 1;
 
-  const uint32_t* bmA = a.bm_a + (int64_t)h * a.bm_stride;
+  // heads packed into the rows of a sparse single-token tile: the unit's "head" is the KV head, the
+  // block bitmaps and column sets are those of head ps_h0 + j of the group (j = row of the tile)
+  const bool ps = BATCH && a.packed_sparse;
+  const int ps_h0 = h * a.group_rows;
+  const int ps_vt = (a.v_budget + 63) >> 6;   // vertical tiles per head at most; tile index = j * ps_vt + vt
+  const uint32_t* bmA = a.bm_a + (int64_t)(ps ? ps_h0 : h) * a.bm_stride;
   const int seg_shift = __builtin_amdgcn_readfirstlane((int)bmA[a.bm_words - 1]);  // sparser list, longer sync segments
   const uint32_t* ent_h = a.ent + (int64_t)h * a.ent_stride;
-  const int32_t* vidx_h = a.v_idx ? a.v_idx + (int64_t)h * a.v_budget : nullptr;
-  const int vcnt = a.v_idx ? __builtin_amdgcn_readfirstlane(a.v_cnt[h]) : 0;
+  const uint32_t* hm_h = ps ? a.hm + (int64_t)h * a.ent_stride : nullptr;
+  const int32_t* vidx_h = a.v_idx ? a.v_idx + (int64_t)(ps ? ps_h0 : h) * a.v_budget : nullptr;
+  const int vcnt = a.v_idx ? __builtin_amdgcn_readfirstlane(a.v_cnt[ps ? ps_h0 : h]) : 0;
   const int n_vt = (vcnt + 63) >> 6;
+  bool row_live = true;   // packed sparse: this lane's row (head) takes part in the current tile
   const int cc_last = m0 + NQB - 1;  // entry cc stands for key block m0 + (NQB - 1) - cc >= 0
 
   const __bf16* kbase = a.k + (int64_t)g * a.k_stride_head;
@@ -411,7 +447,17 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     ei0 = lo;
   }
   uint32_t ecache = ent_h[(ei0 & ~63) + lane], ecache_nx = ent_h[(ei0 & ~63) + 64 + lane];
+  uint32_t hcache = 0, hcache_nx = 0;   // packed sparse: the head masks of the same entries
+  if constexpr (BATCH) {
+    if (ps) { hcache = hm_h[(ei0 & ~63) + lane]; hcache_nx = hm_h[(ei0 & ~63) + 64 + lane]; }
+  }
   int ei = ei0 - 1;
+  // (packed sparse) column set, count and block bitmap of head j of the group
+  auto ps_head = [&](int j, const int32_t*& vi, int& vc, const uint32_t*& bm) {
+    vi = a.v_idx + (int64_t)(ps_h0 + j) * a.v_budget;
+    vc = __builtin_amdgcn_readfirstlane(a.v_cnt[ps_h0 + j]);
+    bm = a.bm_a + (int64_t)(ps_h0 + j) * a.bm_stride;
+  };
   auto advance = [&](int& kind, int& idx, int& mask) {
     int k2 = kind, i2 = idx, m2 = 0;
     if (k2 == 0) {
@@ -419,11 +465,17 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
       if (__builtin_expect((ei & 63) == 0 && ei > ei0, 0)) {
         ecache = ecache_nx;
         ecache_nx = ent_h[(ei & ~63) + 64 + lane];
+        if constexpr (BATCH) {
+          if (ps) { hcache = hcache_nx; hcache_nx = hm_h[(ei & ~63) + 64 + lane]; }
+        }
       }
       const uint32_t e = __builtin_amdgcn_readlane(ecache, ei & 63);
       const int cc = (int)(e >> 4);
       if (cc <= cc_end) {
         i2 = cc; m2 = (int)(e & 15u);
+        if constexpr (BATCH) {
+          if (ps) m2 |= (int)((__builtin_amdgcn_readlane(hcache, ei & 63) & 0xFFFFu) << 4);
+        }
         enter_segment(((cc_last - cc) / a.sync_blocks) >> seg_shift, true);
       } else {
         k2 = 1; i2 = sp - vstep;
@@ -431,10 +483,25 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
       }
     }
     if (k2 == 1) {
+      if (BATCH && ps) {
+        // tiles of head 0, then of head 1, ...: the next one (in steps of vstep) that exists and has a
+        // column the token can see
+        int tl = i2 + vstep;
+        bool more = false;
+        while (tl < a.group_rows * ps_vt) {
+          const int j = tl / ps_vt, vt = tl - j * ps_vt;
+          const int32_t* vi; int vc; const uint32_t* bm;
+          ps_head(j, vi, vc, bm);
+          if (64 * vt < vc && (int64_t)__builtin_amdgcn_readfirstlane(vi[64 * vt]) <= last_pos) { more = true; break; }
+          tl += vstep;
+        }
+        if (more) i2 = tl; else { k2 = 2; i2 = 0; }
+      } else {
       const int vt = i2 + vstep;
       bool more = vt < n_vt;
       if (more) more = (int64_t)__builtin_amdgcn_readfirstlane(vidx_h[64 * vt]) <= last_pos;
       if (more) i2 = vt; else { k2 = 2; i2 = 0; }
+      }
     }
     // the descriptor is uniform by construction; say so, so that it lives in scalar registers
     kind = __builtin_amdgcn_readfirstlane(k2);
@@ -446,6 +513,13 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     if (kind == 0) {
       int64_t j = (int64_t)(m0 - (idx - (NQB - 1))) * 64 + r;
       return j < n_k ? j : n_k - 1;
+    }
+    if (BATCH && ps) {
+      const int j = idx / ps_vt;
+      const int32_t* vi; int vc; const uint32_t* bm;
+      ps_head(j, vi, vc, bm);
+      const int pos = 64 * (idx - j * ps_vt) + r;
+      return pos < vc ? (int64_t)vi[pos] : 0;
     }
     int pos = 64 * idx + r;
     return pos < vcnt ? (int64_t)vidx_h[pos] : 0;
@@ -668,6 +742,12 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
       apply_mask(s0, 0);
       apply_mask(s1, 1);
     }
+    if constexpr (BATCH) {
+      if (ps && !row_live) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) { s0[x] = -INFINITY; s1[x] = -INFINITY; }
+      }
+    }
     float mx = fmaxf(block_max(s0), block_max(s1));
     mx = fmaxf(mx, __shfl_xor(mx, 32)) * c;
     if (!have_max || __any(mx > m_o + 64.f)) {
@@ -844,6 +924,30 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     part = wave_valid && !last;
     diag = false;
     bool usable = false;  // vertical tile: this lane's key can be used by some row of the block
+    if (BATCH && ps && !last) {
+      // heads packed into rows, every head with its own lists: every tile takes the masked path
+      if (cur_kind == 0) {
+        part = part && (cur_mask & 1);
+        diag = cur_idx - (NQB - 1) + t == 0;
+        row_live = il < kPackedSparseMaxGroup && (((cur_mask >> 4) >> il) & 1);
+        need_s[wv * 64 + lane] = 0;           // no key of a slash tile is masked (the diagonal tile masks by position)
+      } else {
+        const int jh = cur_idx / ps_vt;       // the head whose columns this tile gathers
+        const int32_t* vi; int vc; const uint32_t* bm;
+        ps_head(jh, vi, vc, bm);
+        const int pos = 64 * (cur_idx - jh * ps_vt) + lane;
+        const int j = vidx_s[buf * 64 + lane];
+        const int ad = (m0 + t) - (j >> 6);
+        int need = 64;   // all rows stand at the token's position: a column is usable or not
+        if (pos < vc && ad >= 0 && !bm_test(bm, ad) && !(ad == 0 && (j & 63) > a.pos_in_block)) need = 0;
+        need_s[wv * 64 + lane] = (uint8_t)need;
+        usable = need < 64;
+        part = part && __ballot(usable) != 0;
+        row_live = il == jh;
+      }
+      part = part && __ballot(row_live) != 0;
+      vert = true;
+    } else {
     if (__builtin_expect(cur_kind == 0, 1)) {
       part = part && ((cur_mask >> t) & 1);
       diag = cur_idx - (NQB - 1) + t == 0;  // block diagonal 0 of (query block t, this key block)
@@ -858,6 +962,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
       part = part && __ballot(usable) != 0;
     }
     vert = cur_kind == 1;
+    }
     if constexpr (DCA) {
       // which rotation of Q meets this tile's keys (section 5.1, DCA paragraph): keys of the
       // query block's own chunk the intra-chunk one; keys of the chunk before it, closer than
@@ -1080,6 +1185,64 @@ __global__ __launch_bounds__(256) void k_build_blocklist(const int32_t* s_idx, c
     A[n_words - 1] = (uint32_t)shift;
     A[n_words - 2] = running;  // length of the list: the head's share of the work (k_attn_schedule)
   }
+}
+
+// Union list of a sparse single-token request whose heads are packed into rows (one workgroup per
+// (request, KV head), after k_build_blocklist has made the bitmaps of the request's heads): the
+// bitmap words of the G heads are OR-ed; every set bit b becomes the entry ((b + 1) << 4) | 1 (key
+// block m0 - b for the one query block of the tile) with, in ent_hm, the heads whose own bitmap has
+// the bit.  Ascending, sentinels to the end of the row.  Requests of any other kind are left alone.
+__global__ __launch_bounds__(256) void k_build_union(const vs_request* req, int n_q_heads, int n_kv_heads,
+                                                     int64_t max_q_len, int64_t max_n_k, int n_words, int ent_stride,
+                                                     const uint32_t* bm_a, uint32_t* bm_u, uint32_t* ent_u,
+                                                     uint32_t* ent_hm) {
+  const int r = blockIdx.x / n_kv_heads, g = blockIdx.x % n_kv_heads;
+  const int G = n_q_heads / n_kv_heads;
+  const vs_request rq = req[r];
+  if (rq.q_len != 1 || rq.q_len > max_q_len || rq.q_start < 0 || rq.q_start + rq.q_len > max_n_k) return;
+  if (!rq.s_idx || !rq.s_cnt || G < 2 || G > kPackedSparseMaxGroup) return;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const uint32_t* A0 = bm_a + ((int64_t)r * n_q_heads + (int64_t)g * G) * n_words;   // bitmaps of the group's heads
+  uint32_t* U = bm_u + (int64_t)blockIdx.x * n_words;
+  uint32_t* E = ent_u + (int64_t)blockIdx.x * ent_stride;
+  uint32_t* M = ent_hm + (int64_t)blockIdx.x * ent_stride;
+  const int n_bits = 32 * (n_words - 2);   // the last two words of a head's bitmap row hold other things
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t running;
+  if (tid == 0) running = 0;
+  __syncthreads();
+  for (int w0 = 0; w0 < n_words - 2; w0 += 256) {
+    const int w = w0 + tid;
+    uint32_t u = 0;
+    if (w < n_words - 2)
+      for (int j = 0; j < G; ++j) u |= A0[(int64_t)j * n_words + w];
+    if (w < n_words - 2) U[w] = u;
+    const uint32_t c = __popc(u);
+    uint32_t inc = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t y = __shfl_up(inc, d);
+      if (lane >= d) inc += y;
+    }
+    if (lane == 63) wsum[wv] = inc;
+    __syncthreads();
+    uint32_t pos = running + inc - c;
+    for (int x = 0; x < wv; ++x) pos += wsum[x];
+    while (u) {
+      const int b = __builtin_ctz(u);
+      u &= u - 1;
+      uint32_t hm = 0;
+      for (int j = 0; j < G; ++j) hm |= ((A0[(int64_t)j * n_words + w] >> b) & 1u) << j;
+      E[pos] = ((uint32_t)(32 * w + b + 1) << 4) | 1u;
+      M[pos] = hm;
+      ++pos;
+    }
+    __syncthreads();
+    if (tid == 255) running = pos;
+    __syncthreads();
+  }
+  (void)n_bits;
+  for (int i = running + tid; i < ent_stride; i += 256) { E[i] = kEntSentinel; M[i] = 0; }
 }
 
 // Issued-tile accounting, one workgroup per head: for every query block of the chunk, the
@@ -1446,11 +1609,12 @@ static int batch_rows_cap(const vs_params& p) {
 }
 static int batch_tiles(const vs_params& p) { return (int)ceil_div(p.q_len + kBlock - 1, (int64_t)64 * kAttnQBlocks); }
 int attn_batch_split(const vs_params& p, int n_req) {
-  const int64_t heads = p.q_len == 1 ? p.n_kv_heads : p.n_q_heads;   // single tokens: dense requests pack their heads
-  const int64_t units = (int64_t)n_req * heads * batch_tiles(p);
+  // (a single-token request whose heads are packed into rows turns its G head slots into G times as
+  // many key ranges, so the count of unit slots is the same for every kind of request)
+  const int64_t units = (int64_t)n_req * p.n_q_heads * batch_tiles(p);
   const int64_t n_blk = ceil_div(p.q_start + p.q_len, kBlock);
   int64_t s = 512 / units;
-  const int64_t cap = p.q_len == 1 ? 64 : 16;
+  const int64_t cap = 16;
   if (s > cap) s = cap;
   if (s > n_blk / 16) s = n_blk / 16;
   return s < 1 ? 1 : (int)s;
@@ -1459,8 +1623,10 @@ size_t attn_batch_bytes(const vs_params& p, int n_req) {
   const int64_t n_k = p.q_start + p.q_len;
   const size_t lists = (size_t)n_req * p.n_q_heads;
   const size_t rows = (size_t)n_req * attn_batch_split(p, n_req) * p.n_q_heads * (size_t)batch_rows_cap(p);
+  const size_t ulists = (size_t)n_req * p.n_kv_heads;   // union lists of packed sparse single-token requests
   return align_up(lists * (size_t)bitmap_words(n_k) * 4, 256) + align_up(lists * (size_t)entry_stride(n_k) * 4, 256) +
-         align_up(rows * p.head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256) + 256;
+         align_up(rows * p.head_dim * sizeof(float), 256) + align_up(rows * 2 * sizeof(float), 256) + 256 +
+         align_up(ulists * (size_t)bitmap_words(n_k) * 4, 256) + 2 * align_up(ulists * (size_t)entry_stride(n_k) * 4, 256);
 }
 
 hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int n_req, void* ws, hipStream_t st) {
@@ -1482,6 +1648,14 @@ hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int
   a.part_ml = (float*)w;
   w += align_up(rows * 2 * sizeof(float), 256);
   a.arrive = (uint32_t*)w;   // unused by the key-split kernel; one valid word
+  w += 256;
+  const size_t ulists = (size_t)n_req * p.n_kv_heads;
+  a.bm_u = (uint32_t*)w;
+  w += align_up(ulists * (size_t)words * 4, 256);
+  uint32_t* ent_u = (uint32_t*)w;
+  w += align_up(ulists * (size_t)ent_stride * 4, 256);
+  uint32_t* ent_hm = (uint32_t*)w;
+  a.ent_u = ent_u; a.ent_hm = ent_hm;
   a.n_sync = 1; a.sync_blocks = 1 << 30; a.sched = nullptr; a.n_gr = 0;
   a.q_stride_tok = p.q_stride_tok; a.q_stride_head = p.q_stride_head;
   a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
@@ -1508,6 +1682,11 @@ hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int
   hipLaunchKernelGGL((k_build_blocklist<NQB>), dim3((unsigned)lists), dim3(256), 0, st, (const int32_t*)nullptr,
                      (const int32_t*)nullptr, p.slash_budget, 0, 0, (int)words, (int)ent_stride, bm_a, ent, req,
                      (int)p.n_q_heads, (int64_t)p.q_len, n_k);
+  if (a.group > 1 && a.group <= kPackedSparseMaxGroup)
+    hipLaunchKernelGGL(k_build_union, dim3((unsigned)ulists), dim3(256), 0, st, req, (int)p.n_q_heads,
+                       (int)p.n_kv_heads, (int64_t)p.q_len, n_k, (int)words, (int)ent_stride, bm_a, a.bm_u, ent_u, ent_hm);
+  else
+    a.ent_u = nullptr;   // no grouped queries (or too many heads per group for the row masks): nothing to pack
   const dim3 grid((unsigned)a.n_wg), block(128 * NQB);
   const dim3 cgrid((unsigned)ceil_div(a.rows_cap, 4), (unsigned)a.n_q_heads, (unsigned)n_req);
   if (p.head_dim == 128) {
@@ -1518,6 +1697,26 @@ hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int
     hipLaunchKernelGGL((k_attn_combine<64, true>), cgrid, dim3(256), 0, st, a);
   }
   return hipGetLastError();
+}
+
+// Sparse attention of one token with grouped queries through the batch machinery (one request):
+// the heads of a KV group share a tile and the walk of the union of their lists, so K and V are
+// read once per group.  The request's descriptor is written into the workspace by a kernel.
+bool attn_single_token_packs(const vs_params& p) {
+  const int G = p.n_q_heads / p.n_kv_heads;
+  return p.q_len == 1 && G > 1 && G <= kPackedSparseMaxGroup;
+}
+size_t attn_single_token_bytes(const vs_params& p) { return 256 + attn_batch_bytes(p, 1); }
+__global__ void k_write_request(vs_request* dst, const vs_request rq) { *dst = rq; }
+hipError_t launch_attention_single_token(const vs_params& p, const void* q, const void* k, const void* v,
+                                         const int32_t* v_idx, const int32_t* v_cnt, const int32_t* s_idx,
+                                         const int32_t* s_cnt, void* out, float* lse, void* ws, hipStream_t st) {
+  vs_request rq;
+  rq.q = q; rq.k = k; rq.v = v; rq.out = out; rq.lse = lse;
+  rq.v_idx = v_idx; rq.v_cnt = v_cnt; rq.s_idx = s_idx; rq.s_cnt = s_cnt;
+  rq.q_start = p.q_start; rq.q_len = p.q_len;
+  hipLaunchKernelGGL(k_write_request, dim3(1), dim3(1), 0, st, (vs_request*)ws, rq);
+  return launch_attention_batch(p, (const vs_request*)ws, 1, (char*)ws + 256, st);
 }
 
 hipError_t launch_count_tiles(const vs_params& p, const int32_t* v_idx, const int32_t* v_cnt,

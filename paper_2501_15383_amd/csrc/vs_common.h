@@ -78,6 +78,12 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
 // p.q_start + p.q_len = the most keys any request sees; req is a device array
 size_t attn_batch_bytes(const vs_params& p, int n_req);
 hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int n_req, void* ws, hipStream_t st);
+// sparse attention of a single token with 2..16 query heads per KV head runs as a batch of one
+bool attn_single_token_packs(const vs_params& p);
+size_t attn_single_token_bytes(const vs_params& p);
+hipError_t launch_attention_single_token(const vs_params& p, const void* q, const void* k, const void* v,
+                                         const int32_t* v_idx, const int32_t* v_cnt, const int32_t* s_idx,
+                                         const int32_t* s_cnt, void* out, float* lse, void* ws, hipStream_t st);
 size_t attn_sync_bytes(const vs_params& p);
 // key split of short chunks: number of ranges (1 = none) and bytes of partial results
 int attn_split(const vs_params& p, bool dense);
