@@ -28,6 +28,7 @@ run checks the expression.  WRITE_SIZE is in KiB and matches the copy one to one
 
     python3 bench_counters.py [gpurun_out/prof]     writes profiles/vs_kernels_7b_1m_last_chunk.txt
                                                      and profiles/traffic_k_attention_7b_1m.json
+    python3 bench_counters.py --others [gpurun_out/prof]   writes profiles/vs_kernels_other_workloads.txt (see others())
 """
 import collections
 import csv
@@ -69,7 +70,47 @@ def rd_bytes(c):
     return 32 * n32 + 128 * n128 + 64 * (n - n32 - n128)
 
 
+OTHERS = [("dense_7b_64k", "--workload dense_7b_64k"), ("7b_128k", "--workload 7b_128k"), ("14b_1m", "--workload 14b_1m"),
+          ("7b_1m_local", "--workload 7b_1m_local"), ("7b_1m_dca", "--workload 7b_1m_dca"),
+          ("rows64", "--chunk-rows 64"), ("rows1024", "--chunk-rows 1024")]
+
+
+def others(base):
+    """profiles/vs_kernels_other_workloads.txt from the kernel traces kt_<name> of the other workloads:
+         rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt_<name>
+                   -- python3 bench.py <switches> --steps 3 --warmup 1 --no-cpu --no-extras"""
+    out = ["# rocprofv3 kernel traces of the other workloads (one MI355X; raw outputs stay under gpurun_out/; written by",
+           "# bench_counters.py --others).  Each block: the command, the kernels of the library with their launch times over the",
+           "# run, and the bench.py line of the same run.  A run is 1 warm-up + 3 timed chunk steps (+ 3 dense-kernel launches",
+           "# where the workload is sparse), so the k_attention rows mix sparse and dense launches: min / max separate them.", ""]
+    for name, sw in OTHERS:
+        if not glob.glob(f"{base}/kt_{name}/**/*_kernel_trace.csv", recursive=True):
+            continue
+        out += [f"## {name}",
+                f"command: rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof/kt_{name} -- python3 bench.py "
+                f"{sw} --steps 3 --warmup 1 --no-cpu --no-extras"]
+        per = collections.OrderedDict()
+        for r in csv.DictReader(open(one(f"{base}/kt_{name}/**/*_kernel_trace.csv"))):
+            if "vs::" in r["Kernel_Name"]:
+                per.setdefault(r["Kernel_Name"], []).append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e6)
+        out.append(f"{'kernel':62s} {'calls':>5s} {'avg ms':>10s} {'min ms':>10s} {'max ms':>10s}")
+        for n, v in sorted(per.items(), key=lambda x: -sum(x[1])):
+            out.append(f"{n[:62]:62s} {len(v):5d} {sum(v) / len(v):10.3f} {min(v):10.3f} {max(v):10.3f}")
+        d = bench_line(f"{base}/kt_{name}.log")
+        ph = d["phases_ms"]
+        line = (f"bench.py line: {d['value']:.2f} ms per chunk = estimate {ph['estimate']:.2f} + select {ph['select']:.2f} + sparse "
+                f"attention {ph['sparse_attention']:.2f}; {d['config']['workload']}; issued tiles {d['tiles']['slash'] + d['tiles']['vertical'] or d['tiles']['dense_equivalent']}"
+                f" (computed fraction {d['tiles']['computed_fraction']:.3f}), {d['effective_tflops']:.0f} TFLOP/s on issued tiles")
+        if d.get("dense_ms"):
+            line += f"; dense kernel {d['dense_ms']:.2f} ms = {d['dense_tflops']:.0f} TFLOP/s, speed-up {d['speedup_vs_dense']:.2f}"
+        out += [line, ""]
+    open(os.path.join(ROOT, "profiles", "vs_kernels_other_workloads.txt"), "w").write("\n".join(out) + "\n")
+    print("\n".join(out))
+
+
 def main():
+    if len(sys.argv) > 1 and sys.argv[1] == "--others":
+        return others(sys.argv[2] if len(sys.argv) > 2 else os.path.join(ROOT, "gpurun_out", "prof"))
     base = sys.argv[1] if len(sys.argv) > 1 else os.path.join(ROOT, "gpurun_out", "prof")
     sys.path.insert(0, ROOT)
     import bench

@@ -287,7 +287,10 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     gr = __builtin_amdgcn_readfirstlane(a0.sched[grp * n_gr + rnd]);
     if (gr < 0) break;
   }
-  AttnArgs a = a0;  // this round's view of the arguments (BATCH: those of the unit's request)
+  // this round's view of the arguments: the kernel's own, or (BATCH) those of the unit's request
+  AttnArgs a_req;
+  if constexpr (BATCH) a_req = a0;
+  const AttnArgs& a = BATCH ? a_req : a0;
   int h, qt, sp = 0;
   if constexpr (BATCH) {
     const int per_head = a0.n_qtiles * a0.n_split, per_req = per_head * a0.n_q_heads;
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     v -= h * per_head;
     qt = v / a0.n_split;
     sp = v - qt * a0.n_split;
-    if (!batch_view(a0, r, a)) continue;
+    if (!batch_view(a0, r, a_req)) continue;
     if (a.same_pos) {
       // heads packed into rows: the unit slots of the G heads of a group become G times as many key
       // ranges of the group's one tile
