@@ -303,7 +303,7 @@ int vs_plan_chunks(int64_t n_ctx, int32_t n_chunks, int32_t model,
  * made under a setting that needs more workspace than it is given returns
  * VS_ERR_WORKSPACE.  Returns VS_OK or VS_ERR_INVALID_ARG.
  *   VS_OPT_ATTN_SEGMENT_BLOCKS  value = number of 64-key blocks per sync segment of the
- *     attention launches, 0 = automatic.  The attention kernels are persistent;
+ *     attention launches (rounded down to a power of two), 0 = automatic.  The attention kernels are persistent;
  *     workgroups that walk the same head keep within two sync segments of each
  *     other (bounded waits on counters in the workspace) so that their K/V
  *     blocks are shared through the L2.  Only the timing depends on it.  The

@@ -76,6 +76,18 @@ def build(force: bool = False, verbose: bool = False, extra_flags: list[str] | N
     return lib
 
 
+def build_ceiling(force: bool = False) -> str:
+    """libvs_ceiling.so: the instruction-mix ceiling kernels of csrc/vs_ceiling.hip (a measurement aid that
+    bench_ceiling.py runs; not linked into libvs.so)."""
+    src, lib = os.path.join(CSRC, "vs_ceiling.hip"), os.path.join(HERE, "libvs_ceiling.so")
+    if force or _stale(lib, [src]):
+        cmd = [_hipcc()] + [f for f in FLAGS if f != "-Wall"] + ["-shared", "-o", lib, src]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed for vs_ceiling.hip:\n" + r.stderr)
+    return lib
+
+
 if __name__ == "__main__":
     # python -m paper_2501_15383_amd.build [--force] [--variant NAME -DSWITCH ...]
     argv = sys.argv[1:]

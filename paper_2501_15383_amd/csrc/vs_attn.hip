@@ -102,8 +102,8 @@ struct AttnArgs {
   // that follow, so that only the very last round can have idle members.
   int32_t n_wg, members, n_full, n_rem;
   // pace keeping: arrive[g][s] counts the members of group g that are done with key blocks
-  // [s * sync_blocks, (s + 1) * sync_blocks) over all rounds so far
-  int32_t sync_blocks, n_sync;
+  // [s * sync_blocks, (s + 1) * sync_blocks) over all rounds so far; sync_blocks = 1 << sync_shift
+  int32_t sync_blocks, sync_shift, n_sync;
   uint32_t* arrive;
   // sched[g][r]: the group-round that group g works on in its r-th round, -1 = none left
   // (written by k_attn_schedule from the lengths of the heads' block lists; n_gr entries per group)
@@ -234,6 +234,8 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 //                   (half of the LDS operand reads gone, same MFMA count)
 //   VS_X_NOCOPY     the global -> LDS copies of whole key blocks are skipped after the first two
 //   VS_X_NOBARRIER  no workgroup barrier at the end of a step
+//   VS_X_TIGHT      dense list only: the steady-state steps run in a loop with no list reads, no
+//                   tile classification and no bookkeeping beyond the pace keeping (right results)
 // They split the time of a step into what the arithmetic stream, the operand reads, the copies
 // and the barrier cost.
 template <int D, int NQB, bool DCA, bool SPLIT, bool BATCH = false>
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
   const int n_gr = SPLIT ? (a0.n_qtiles * a0.n_split * a0.n_q_heads * (BATCH ? a0.n_req : 1) + a0.members - 1) / a0.members
                          : n_full_gr + (a0.n_rem * a0.n_q_heads + a0.members - 1) / a0.members;
   uint32_t* const arr = a0.arrive + (int64_t)grp * a0.n_sync;
-  const int s_glob_top = (int)((a0.n_k - 1) / 64) / a0.sync_blocks;  // highest sync segment of the chunk
+  const int s_glob_top = (int)((a0.n_k - 1) / 64) >> a0.sync_shift;  // highest sync segment of the chunk
   for (int rnd = 0; SPLIT ? rnd * 8 + grp < n_gr : rnd < n_gr; ++rnd) {
   int gr = rnd * 8 + grp;
   if constexpr (!SPLIT) {
@@ -479,7 +481,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
         if constexpr (BATCH) {
           if (ps) m2 |= (int)((__builtin_amdgcn_readlane(hcache, ei & 63) & 0xFFFFu) << 4);
         }
-        enter_segment(((cc_last - cc) / a.sync_blocks) >> seg_shift, true);
+        enter_segment((cc_last - cc) >> (a.sync_shift + seg_shift), true);
       } else {
         k2 = 1; i2 = sp - vstep;
         enter_segment(-1, false);  // the slash walk is over
@@ -1031,6 +1033,26 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
     classify();
     // steady state: runs of steps in which this wave multiplies tile i and folds in tile i - 1
     while (__builtin_expect(pend && part && !(diag || vert || !have_max), 1)) {
+#ifdef VS_X_TIGHT
+      // timing diagnostic (dense list only: entry index = cc, every mask full): the steps of the walk with
+      // nothing but the fused arithmetic, the copies, the pace keeping and the barrier
+      if (!DCA && !SPLIT && a.bm_stride == 0 && cur_kind == 0 && nxt_kind == 0 && cur_idx >= NQB) {
+        while (cur_idx + 2 <= cc_end) {
+          const int ci = cur_idx;
+          auto launch = [&]() { issue_k(0, ci + 1, buf ^ 1); issue_v(0, ci, buf); };
+          fused(Ks + buf * TILE, Vs + (buf ^ 1) * TILE, launch);
+          enter_segment((cc_last - (ci + 2)) >> (a.sync_shift + seg_shift), true);
+          wait_copies();
+          __syncthreads();
+          ++cur_idx;
+          buf ^= 1;
+        }
+        nxt_idx = cur_idx + 1; nxt_mask = 3; cur_mask = 3;
+        ei = nxt_idx;
+        ecache = ent_h[(ei & ~63) + lane]; ecache_nx = ent_h[(ei & ~63) + 64 + lane];
+        classify();
+      }
+#endif
       if (__builtin_expect(!fused(kb, vbp, launch_copies), 0)) qk_exact(kb, diag, vert, apply_mask);
       end_step();
       classify();
@@ -1312,7 +1334,11 @@ static std::atomic<int> g_sync_blocks{0};
 void set_attn_segment_blocks(int blocks) { g_sync_blocks.store(blocks < 0 ? 0 : blocks, std::memory_order_relaxed); }
 static int attn_sync_blocks(const vs_params& p) {
   const int forced = g_sync_blocks.load(std::memory_order_relaxed);
-  if (forced > 0) return forced;
+  if (forced > 0) {   // a power of two (rounded down): the kernel finds a block's segment with a shift
+    int sb = 1;
+    while (sb * 2 <= forced) sb *= 2;
+    return sb;
+  }
   const int per_block = kBlock * p.head_dim * 2 * 2;  // K and V of one KV head
   int sb = 1;
   while (sb * 2 * 3 * per_block <= (6 << 20)) sb *= 2;
@@ -1570,6 +1596,8 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
   a.n_full = a.n_qtiles / members;
   a.n_rem = a.n_qtiles - a.n_full * members;
   a.sync_blocks = attn_sync_blocks(p);
+  a.sync_shift = 0;
+  while ((1 << (a.sync_shift + 1)) <= a.sync_blocks) ++a.sync_shift;
   a.n_sync = (int)ceil_div(ceil_div(p.q_start + p.q_len, kBlock), a.sync_blocks);
   a.arrive = (uint32_t*)sync_ws;
   a.n_gr = a.n_full * a.n_q_heads + (int)ceil_div((int64_t)a.n_rem * a.n_q_heads, a.members);
@@ -1659,7 +1687,7 @@ hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int
   w += align_up(ulists * (size_t)ent_stride * 4, 256);
   uint32_t* ent_hm = (uint32_t*)w;
   a.ent_u = ent_u; a.ent_hm = ent_hm;
-  a.n_sync = 1; a.sync_blocks = 1 << 30; a.sched = nullptr; a.n_gr = 0;
+  a.n_sync = 1; a.sync_blocks = 1 << 30; a.sync_shift = 30; a.sched = nullptr; a.n_gr = 0;
   a.q_stride_tok = p.q_stride_tok; a.q_stride_head = p.q_stride_head;
   a.k_stride_tok = p.k_stride_tok; a.k_stride_head = p.k_stride_head;
   a.v_stride_tok = p.v_stride_tok; a.v_stride_head = p.v_stride_head;
