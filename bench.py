@@ -265,6 +265,8 @@ def main():
                     help="only the timed chunk: no gather probe, no whole-layer prefill, no 14B chunk, no batched requests")
     ap.add_argument("--gather-probe", action="store_true", help="run the gather probe even with --no-extras")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--kv-head-major", action="store_true",
+                    help="allocate the K and V caches as [Hkv][n_k][D] (each KV head contiguous) instead of [n_k][Hkv][D]")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--calib-copy", action="store_true",
@@ -300,6 +302,8 @@ def main():
 
     t0 = time.time()
     K, V = vsgen.make_kv(w, n_k, device=dev)
+    if args.kv_head_major:   # same values, another placement: the calls take the strides from the tensors
+        K, V = (t.permute(1, 0, 2).contiguous().permute(1, 0, 2) for t in (K, V))
     dca = sel = None   # Dual Chunk Attention workloads: (q_succ, q_inter, chunk, window) next to the intra-chunk Q,
     if w.dca_chunk > 0:  # for the attention and (continuous relative positions) for the selection
         Q, q_succ, q_inter = vsgen.make_q_dca(w, s, s + C, device=dev)
