@@ -233,6 +233,7 @@ __device__ __forceinline__ uint32_t lds_address(const void* p) {
 //   VS_X_NOVLDS     the V^T fragments of the fused step come from a register instead of LDS
 //                   (half of the LDS operand reads gone, same MFMA count)
 //   VS_X_NOCOPY     the global -> LDS copies of whole key blocks are skipped after the first two
+//   VS_X_SAMEBLK    every whole-block copy reads key block 0 or 1 of the head (always in the L2)
 //   VS_X_NOBARRIER  no workgroup barrier at the end of a step
 //   VS_X_TIGHT      dense list only: the steady-state steps run in a loop with no list reads, no
 //                   tile classification and no bookkeeping beyond the pace keeping (right results)
@@ -557,7 +558,11 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
 #ifdef VS_X_NOCOPY
         if (ei > ei0 + 1) return;
 #endif
+#ifdef VS_X_SAMEBLK
+        const char* kt = (const char*)kbase + (j0 & 64) * a.k_stride_tok * 2;
+#else
         const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
+#endif
         if constexpr (GPW == 4) dma16x4(kdst, kt, koff[0], koff[1], koff[2], koff[3], WAVES * 1024);
         else dma16x2(kdst, kt, koff[0], koff[1], WAVES * 1024);
       }
@@ -581,7 +586,11 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
 #ifdef VS_X_NOCOPY
         if (ei > ei0 + 1) return;
 #endif
+#ifdef VS_X_SAMEBLK
+        const char* vt = (const char*)vbase + (j0 & 64) * a.v_stride_tok * 2;
+#else
         const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
+#endif
         if constexpr (GPW == 4) dma16x4(vdst, vt, voff[0], voff[1], voff[2], voff[3], WAVES * 1024);
         else dma16x2(vdst, vt, voff[0], voff[1], WAVES * 1024);
       }
