@@ -50,7 +50,7 @@ struct EstArgs {
 };
 
 template <int D, int NH, int PASS, bool DCA>
-__global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
+__global__ __launch_bounds__(128 * NH, DCA ? 1 : 4) void k_estimate(const EstArgs a) {
   constexpr int NW = 2 * NH, NT = 64 * NW, KS = D + 8, DCH = D / 8, DSTEPS = D / 16;
   constexpr int KPT = (64 * DCH + NT - 1) / NT;
   constexpr int STRIP = kEstRange + 64;
@@ -200,8 +200,10 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
       // a tile whose pairs are of several patterns is taken once per rotation, each pass keeping
       // the pairs of its own pattern (every sum below is additive over the passes)
       // (the body exists twice, so that the common one-rotation tiles carry none of the pattern tests)
-      auto blocks = [&](auto masked, const int rot) {
+      // (... and once more with and without the causal mask, which only the last tiles of the keys need)
+      auto blocks = [&](auto masked, auto causal, const int rot) {
       constexpr bool MASKED = decltype(masked)::value;
+      constexpr bool CAUSAL = decltype(causal)::value;
 #pragma unroll
       for (int jb = 0; jb < 2; ++jb) {
         const __bf16* const kfp = &Ks[buf][(32 * jb + (lane & 31)) * KS + 8 * hh];
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
             for (int x = 0; x < 16; ++x)
               if (var_of(ck_rel, dist0, lane & 31, 32 * jb + 8 * (x >> 2) + 4 * hh + (x & 3)) != rot) s[x] = -INFINITY;
           }
-          if (need_mask) {
+          if (CAUSAL) {
             // key j is masked for query r iff j - p0 > r; dr = r - (j0 - p0) - 32 jb - 4 hh
             const int dr = 32 * ib + (lane & 31) - (int)(j0 - a.p0) - 32 * jb - 4 * hh;
 #pragma unroll
@@ -252,28 +254,35 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
           }
           // causal mask in 32 bits: key j is masked for query i iff j - p0 > i; dj = j - p0 - 4 hh
           // is compared with the uniform 32 ib + q0 (only tiles at the end of the keys need it)
-          const int dj = need_mask ? (int)(j0 - a.p0) + 32 * jb + (lane & 31) - 4 * hh : 0;
+          const int dj = CAUSAL ? (int)(j0 - a.p0) + 32 * jb + (lane & 31) - 4 * hh : 0;
           // Diagonal sums of this 32 x 32 block without atomics.  Element x of a lane is
           // query q = 8 (x/4) + 4 hh + (x%4) of the block against key t = lane % 32, on block
           // diagonal e = q - t.  Rotating the 32-lane vector of element x by q lanes (inside
           // each half-wave) puts e = -t (no wrap) or e = 32 - t (wrapped) into lane t for
           // every x, so two accumulators per lane collect all 63 diagonals of the block.
-          float colsum = 0.f, dneg = 0.f, dpos = 0.f;
+          // (all of a lane's elements go into `dall`, the wrapped ones into `dpos` as well: the
+          // unwrapped sum is the difference, exact in the lanes that never or always wrap)
+          float colsum = 0.f, dall = 0.f, dpos = 0.f;
           const int t4 = (lane & 31) + 4 * hh;
 #pragma unroll
           for (int x = 0; x < 16; ++x) {
             const int q0 = 8 * (x >> 2) + (x & 3);
             const f32x4 lse4 = lse_q[2 * (x >> 2)];
             float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[x], a.scale_log2, -lse4[x & 3]));
-            if (need_mask && dj > 32 * ib + q0) p = 0.f;
+            if (CAUSAL && dj > 32 * ib + q0) p = 0.f;
             if (MASKED && var_of(ck_rel, dist0, q0 + 4 * hh, 32 * jb + (lane & 31)) != rot) p = 0.f;  // another pass's pair
             colsum += p;
             const int src = ((t4 + q0) & 31) | (lane & 32);
+#ifdef VS_X_EST_NODIAG   // timing diagnostic, never defined in the library that ships (results are wrong): no lane rotation
+            const float r = p; (void)src;
+#else
             const float r = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, p)));
+#endif
             const bool wrapped = t4 + q0 >= 32;
-            dneg += wrapped ? 0.f : r;
+            dall += r;
             dpos += wrapped ? r : 0.f;
           }
+          float dneg = dall - dpos;
           dneg += __shfl_xor(dneg, 32);
           dpos += __shfl_xor(dpos, 32);
           // strip index of (query i, key jl) is i - jl + (kEstRange - 1); the strip is private
@@ -288,12 +297,13 @@ __global__ __launch_bounds__(128 * NH) void k_estimate(const EstArgs a) {
       }
       };
       if (!multi) {
-        blocks(std::false_type{}, 0);
+        if (need_mask) blocks(std::false_type{}, std::true_type{}, 0);
+        else blocks(std::false_type{}, std::false_type{}, 0);
       } else {
         for (int rot = 0; rot < 3; ++rot) {
           if (!((need >> rot) & 1u)) continue;
           if (q_var != rot) load_q(rot);
-          blocks(std::true_type{}, rot);
+          blocks(std::true_type{}, std::true_type{}, rot);
         }
       }
       if (PASS == 1) {
