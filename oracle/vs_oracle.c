@@ -34,9 +34,10 @@
  * recall in (0,1], selection against a stable sort; the Dual Chunk Attention
  * variants against a hand-written pattern matrix, a brute force that reads its
  * patterns from that matrix, and the cases in which they must reduce to the
- * plain functions.  The position lists printed for the figure of "Integrating
- * with DCA" are parity unpinned: the figure itself is missing from the text and
- * the lists alone do not fix chunk length and window.  Accuracy of the sparse
+ * plain functions; the pattern rule also reproduces, with the positions of the
+ * input recipe, the two diagonal lists that the caption of the figure of
+ * "Integrating with DCA" prints (tests/golden/dca_diagonal_lists.txt; chunk
+ * length 5, largest position 7, distance 7).  Accuracy of the sparse
  * result against dense attention on real text is parity unpinned (it needs
  * trained weights and the paper's evaluation suites).
  */

@@ -65,3 +65,37 @@ def test_heavy_tail_and_ranged_sink_counts():
     norms = K.float().norm(dim=-1) / math.sqrt(128)
     frac_big = (norms > 1.6).float().mean().item()      # exp(z) > 1.6 for ~32% of the 5% picked
     assert 0.005 < frac_big < 0.05
+
+
+def test_dca_positions_reproduce_the_diagonal_lists_the_paper_prints():
+    """Section 5.2, "Integrating with DCA": the caption of its figure prints the relative positions along one
+    diagonal in DCA and in the selection of critical tokens.  The pattern of a pair comes from the oracle's
+    rule (vso_dca_region), the positions from the input recipe; together they must give the printed lists."""
+    import os
+    import oracle
+    path = os.path.join(os.path.dirname(__file__), "golden", "dca_diagonal_lists.txt")
+    rows = [[int(x) for x in l.split()] for l in open(path) if l.strip() and not l.startswith("#")]
+    in_dca, in_selection = rows
+    c, w, dist = 5, 3, 7
+    i = torch.arange(0, 20, dtype=torch.int64)
+    key, *q_att = vsgen.dca_positions(i, c, w)
+    key_s, *q_sel, w_sel = vsgen.dca_select_positions(i, c, w)
+    assert torch.equal(key, key_s) and torch.equal(q_att[0], q_sel[0])     # keys and the intra-chunk rotation are shared
+    got_dca, got_sel = [], []
+    for qi in range(14, 6, -1):
+        kj = qi - dist
+        got_dca.append(int(q_att[oracle.dca_region(qi, kj, c, w)][qi] - key[kj]))
+        got_sel.append(int(q_sel[oracle.dca_region(qi, kj, c, w_sel)][qi] - key[kj]))
+    assert got_dca == in_dca
+    assert got_sel == in_selection
+    # and the properties the paragraph states: inside a chunk and inside the local window the true distance, in both
+    for qi in range(20):
+        for kj in range(qi + 1):
+            r = oracle.dca_region(qi, kj, c, w)
+            rel = int(q_att[r][qi] - key[kj])
+            if r < 2:
+                assert rel == qi - kj
+            assert 0 <= rel <= c + w - 1                                   # never beyond the largest position
+            rs = oracle.dca_region(qi, kj, c, w_sel)
+            if rs < 2:
+                assert int(q_sel[rs][qi] - key[kj]) == qi - kj             # adjacent chunks: continuous

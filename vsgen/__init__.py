@@ -243,32 +243,46 @@ def make_q(w: Workload, t0: int, t1: int, device="cpu") -> torch.Tensor:
     return _make_q_at(w, t0, t1, t0, device)
 
 
+def dca_positions(i, chunk: int, window: int):
+    """RoPE positions of Dual Chunk Attention for token indices i (an int64 tensor): the key position and
+    the query's position under the intra-chunk, successive-chunk and inter-chunk pattern (section 5.1, DCA
+    paragraph: distances inside a chunk and inside the local window are kept, every other pair sees the
+    largest position c + w - 1 against the key's position in its own chunk)."""
+    m = i % chunk
+    return m, m, m + chunk, torch.full_like(i, chunk + window - 1)
+
+
+def dca_select_positions(i, chunk: int, window: int):
+    """The same for the SELECTION of critical tokens (section 5.2, "Integrating with DCA": relative
+    positions that stay as consistent as possible along a diagonal): the successive-chunk position
+    (i mod c) + c serves every pair of adjacent chunks, so their relative position is the true distance,
+    and the inter-chunk position moves with the query, (i mod c) + c + w - 1, so that along a diagonal it
+    is constant within a pair of chunks.  With c = 5 and c + w - 1 = 7 this gives the diagonal lists that
+    the caption of the section's figure prints (tests/golden/dca_diagonal_lists.txt).  Returns
+    (key, intra, successive, inter, window to select with = 2c: all of the chunk before the query's)."""
+    m = i % chunk
+    return m, m, m + chunk, m + chunk + window - 1, 2 * chunk
+
+
 def make_q_dca(w: Workload, t0: int, t1: int, device="cpu"):
     """The three rotations of the queries of tokens t0..t1-1 under Dual Chunk Attention:
     (intra-chunk, successive-chunk, inter-chunk), each bf16 [t1-t0][Hq][D]."""
     assert w.dca_chunk > 0
     i = torch.arange(t0, t1, dtype=torch.int64, device=device)
-    return (_make_q_at(w, t0, t1, i % w.dca_chunk, device),
-            _make_q_at(w, t0, t1, i % w.dca_chunk + w.dca_chunk, device),
-            _make_q_at(w, t0, t1, torch.full_like(i, w.dca_chunk + w.dca_window - 1), device))
+    _, intra, succ, inter = dca_positions(i, w.dca_chunk, w.dca_window)
+    return (_make_q_at(w, t0, t1, intra, device), _make_q_at(w, t0, t1, succ, device),
+            _make_q_at(w, t0, t1, inter, device))
 
 
 def make_q_dca_select(w: Workload, t0: int, t1: int, device="cpu"):
     """The rotations the SELECTION of a Dual Chunk Attention workload uses for the successive-chunk
-    and the inter-chunk pattern, and the (chunk, window) that go with them: (q_succ, q_inter, c, 2c).
-    Section 5.2, "Integrating with DCA": the critical tokens are selected with relative positions
-    that stay continuous along a diagonal, the attention itself keeps DCA's own positions.  The
-    paper shows this in a figure that the text does not reproduce; this recipe's reading: for the
-    selection the successive-chunk pattern covers the whole chunk before the query's (window = 2c,
-    queries at (i mod c) + c, so the relative position is the true distance i - j up to 2c - 1), and
-    the inter-chunk pattern sits at the constant 2c - 1 where those distances end -- along a
-    diagonal the relative position is the true distance, then that constant, and never jumps back
-    as it does at the end of DCA's local window.  The intra-chunk rotation is shared with the attention."""
+    and the inter-chunk pattern, and the (chunk, window) that go with them: (q_succ, q_inter, c, 2c);
+    see dca_select_positions.  The intra-chunk rotation is shared with the attention, which keeps
+    DCA's own positions."""
     assert w.dca_chunk > 0
     i = torch.arange(t0, t1, dtype=torch.int64, device=device)
-    c = w.dca_chunk
-    return (_make_q_at(w, t0, t1, i % c + c, device),
-            _make_q_at(w, t0, t1, torch.full_like(i, 2 * c - 1), device), c, 2 * c)
+    _, _, succ, inter, win = dca_select_positions(i, w.dca_chunk, w.dca_window)
+    return (_make_q_at(w, t0, t1, succ, device), _make_q_at(w, t0, t1, inter, device), w.dca_chunk, win)
 
 
 def _make_kv_slab(w: Workload, t0: int, t1: int, device, sinks, mags, u):
