@@ -188,7 +188,7 @@ __device__ __forceinline__ bool bm_test(const uint32_t* bm, int i) {
 // LDS bytes of one workgroup: K and V tiles (unpadded, chunk-swizzled), double-buffered, the
 // gathered column indices of a vertical tile, and per-wave mask thresholds.
 template <int D>
-constexpr int attn_lds_bytes() { return 4 * 64 * D * 2 + 2 * 64 * 4 + 8 * 64; }
+constexpr int attn_lds_bytes() { return 4 * 64 * D * 2 + 2 * 64 * 4 + 4 * kAttnQBlocks * 64; }
 
 // Direct global -> LDS copy, 16 bytes per lane: lane L's bytes land at lds_addr + 16 L
 // (lds_addr is wave-uniform and goes through M0).  Completion is tracked by vmcnt.
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
   __bf16* const Vs = Ks + 2 * TILE;                   // [2][TILE]
   int32_t* const vidx_s = (int32_t*)(Vs + 2 * TILE);  // [2][64]
   uint8_t* const need_s = (uint8_t*)(vidx_s + 2 * 64);  // [waves][64], private to each wave
-  static_assert(2 * (2 * NQB) * 64 <= 8 * 64, "need_s and dcak_s share the 8 x 64 bytes");
+  static_assert(2 * (2 * NQB) * 64 <= 4 * kAttnQBlocks * 64, "need_s and dcak_s share the bytes after vidx_s");
   uint8_t* const dcak_s = need_s + 2 * NQB * 64;        // [waves][64], DCA pattern code of a tile's keys
   const uint32_t ks_addr = lds_address(Ks), vs_addr = lds_address(Vs);
 
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
   const int kch = lc ^ ((r0 / R) % DCH);       // d-chunk it fetches for K (after the swizzle)
   const int vch = lc ^ ((((r0 / R) & 3) << 2) & (DCH - 1));  // ... and for V
   static_assert((WAVES * RPG / R) % DCH == 0 && (WAVES * RPG / R) % 4 == 0, "swizzle must not depend on e");
-  static_assert(GPW == 2 || GPW == 4, "copies of a tile per wave");
+  static_assert(GPW == 1 || GPW == 2 || GPW == 4, "copies of a tile per wave");
   uint32_t koff[GPW], voff[GPW];  // byte offset of this lane's 16 bytes in copy e of a tile
 #pragma unroll
   for (int e = 0; e < GPW; ++e) {
@@ -564,7 +564,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
         const char* kt = (const char*)kbase + j0 * a.k_stride_tok * 2;
 #endif
         if constexpr (GPW == 4) dma16x4(kdst, kt, koff[0], koff[1], koff[2], koff[3], WAVES * 1024);
-        else dma16x2(kdst, kt, koff[0], koff[1], WAVES * 1024);
+        else if constexpr (GPW == 2) dma16x2(kdst, kt, koff[0], koff[1], WAVES * 1024);
+        else dma16_lane_ptr(kdst, kt + koff[0]);
       }
     }
     if (__builtin_expect(!fast, 0)) {
@@ -592,7 +593,8 @@ __global__ __launch_bounds__(128 * NQB, 2) void k_attention(const AttnArgs a0) {
         const char* vt = (const char*)vbase + j0 * a.v_stride_tok * 2;
 #endif
         if constexpr (GPW == 4) dma16x4(vdst, vt, voff[0], voff[1], voff[2], voff[3], WAVES * 1024);
-        else dma16x2(vdst, vt, voff[0], voff[1], WAVES * 1024);
+        else if constexpr (GPW == 2) dma16x2(vdst, vt, voff[0], voff[1], WAVES * 1024);
+        else dma16_lane_ptr(vdst, vt + voff[0]);
       }
     }
     if (__builtin_expect(!fast, 0)) {
@@ -1588,7 +1590,7 @@ hipError_t launch_attention(const vs_params& p, const void* q, const DcaArgs* dc
     const hipError_t e = attn_device_setup(&n_cu);
     if (e != hipSuccess) return e;
   }
-  int members = (2 * n_cu) / 8;
+  int members = ((4 / kAttnQBlocks) * n_cu) / 8;   // resident workgroups per XCD
   if (members < 1) members = 1;
   a.n_split = attn_split(p, dense);
   a.part_o = a.part_ml = nullptr;
@@ -1715,7 +1717,7 @@ hipError_t launch_attention_batch(const vs_params& p, const vs_request* req, int
   hipError_t e = attn_device_setup(&n_cu);
   if (e != hipSuccess) return e;
   const int64_t units = (int64_t)n_req * a.n_q_heads * a.n_qtiles * a.n_split;
-  int members = (2 * n_cu) / 8;
+  int members = ((4 / kAttnQBlocks) * n_cu) / 8;   // resident workgroups per XCD
   if (members < 1) members = 1;
   if (units < 8 * (int64_t)members) members = (int)ceil_div(units, 8);
   a.members = members; a.n_wg = 8 * members; a.n_full = 0; a.n_rem = 0;

@@ -29,7 +29,12 @@ static inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; 
 //   m0 uses key block m0 - c, and query block t of the tile takes part iff mask bit t is set
 //   (diagonal c + t is in A).  The list is padded with sentinels (cc = 0x7FFFFFF) so that a
 //   reader may fetch whole batches of 64 entries without bounds checks.
+#ifdef VS_X_QBLOCKS
+constexpr int kAttnQBlocks = VS_X_QBLOCKS;   // timing experiment (4 = one workgroup of eight waves per compute unit):
+                                             // the prefill paths stay correct, the packed single-token path does not
+#else
 constexpr int kAttnQBlocks = 2;       // query blocks (of 64 rows) per attention workgroup
+#endif
 constexpr uint32_t kEntSentinel = 0x7FFFFFF0u;
 
 struct BlockList {
