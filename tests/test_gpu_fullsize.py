@@ -199,3 +199,49 @@ def test_determinism_at_headline_size():
     torch.cuda.synchronize()
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16)), "vs_prefill_chunk: out differs between two runs"
     assert torch.equal(l1, l2), "vs_prefill_chunk: lse differs between two runs"
+
+
+def test_batched_requests_at_bench_size():
+    """The `batched_requests` rows of bench.py (vs_attn_batch, 7B shape, eight requests against caches of
+    262,144 keys: single-token steps and chunks of 17 to 64 rows, dense and sparse mixed), in the launch
+    bench.py times, on sampled heads and rows; the sparse requests use the index sets the GPU selected."""
+    n_keys = 262144
+    w = vsgen.scaled(vsgen.WORKLOADS["7b_1m"], n_ctx=n_keys)
+    dev = torch.device("cuda:0")
+    K, V = vsgen.make_kv(w, n_keys, device=dev)
+    kh, vh = vsgen.as_u16(K), vsgen.as_u16(V)
+    hq, hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    bv, bs = w.vertical_budget, w.slash_budget
+    heads = np.array([0, 6, 7, 27])
+    rng = np.random.default_rng(2300)
+    for lens, flags in (([1] * 8, [False] * 8), ([1] * 8, [True] * 8),
+                        ([1, 17, 64, 1, 17, 64, 33, 64], [False, True, False, True, False, True, False, True])):
+        reqs = []
+        for i, (c, sp) in enumerate(zip(lens, flags)):
+            s = n_keys - c - 64 * i            # every request at its own position
+            Q = vsgen.make_q(w, s, s + c, device=dev)
+            pb = oracle.Problem(hq, hkv, d, c, s, w.softmax_scale, last_q=w.last_q, vertical_budget=bv, slash_budget=bs,
+                                keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
+            sets = None
+            if sp:
+                vsc, ssc, _ = vs.estimate(chunk_of(pb), Q, K)
+                sets = vs.select(chunk_of(pb), vsc, ssc)
+            reqs.append(dict(q=Q, k=K, v=V, q_start=s, sets=sets, pb=pb,
+                             out=torch.full((c, hq, d), -3.0, dtype=torch.bfloat16, device=dev),
+                             lse=torch.full((hq, c), 7.0, dtype=torch.float32, device=dev)))
+        mx = max(lens)
+        ckb = vs.Chunk(hq, hkv, d, mx, n_keys - mx, w.softmax_scale, vertical_budget=bv, slash_budget=bs)
+        table = vs.request_table(reqs, dev)
+        vs.attn_batch(ckb, table, len(reqs), reqs[0]["q"], K, V, reqs[0]["out"])
+        torch.cuda.synchronize()
+        for i, r in enumerate(reqs):
+            pb = r["pb"]
+            rows = np.array(sorted(set([0, pb.q_len - 1] + rng.choice(pb.q_len, min(3, pb.q_len), replace=False).tolist())))
+            qh = vsgen.as_u16(r["q"])
+            if r["sets"] is None:
+                ref_out, ref_lse = oracle.dense_attention(pb, qh, kh[:pb.n_k], vh[:pb.n_k], heads=heads, rows=rows)
+            else:
+                sh = [x.cpu().numpy() for x in r["sets"]]
+                ref_out, ref_lse = oracle.sparse_attention(pb, qh, kh[:pb.n_k], vh[:pb.n_k], *sh, heads=heads, rows=rows)
+            _check_rows(r["out"], r["lse"], ref_out, ref_lse, heads, rows,
+                        f"request {i} ({'sparse' if r['sets'] is not None else 'dense'}, {pb.q_len} rows at {pb.q_start})")
