@@ -245,3 +245,34 @@ def test_batched_requests_at_bench_size():
                 ref_out, ref_lse = oracle.sparse_attention(pb, qh, kh[:pb.n_k], vh[:pb.n_k], *sh, heads=heads, rows=rows)
             _check_rows(r["out"], r["lse"], ref_out, ref_lse, heads, rows,
                         f"request {i} ({'sparse' if r['sets'] is not None else 'dense'}, {pb.q_len} rows at {pb.q_start})")
+
+
+@pytest.mark.parametrize("rows_in_chunk", [1, 64, 1024])
+def test_short_chunks_at_1m_keys(rows_in_chunk):
+    """The last `rows_in_chunk` tokens of the 1M context (a decode step; the `--chunk-rows` figures of the
+    profiles): the key walk of every (tile, head) is cut into ranges and folded, a single token packs the
+    heads of a KV group into one tile.  Dense and sparse, sampled heads and rows."""
+    w = vsgen.scaled(vsgen.WORKLOADS["7b_1m"], chunk=rows_in_chunk)
+    dev = torch.device("cuda:0")
+    C = rows_in_chunk
+    s, n_k = w.n_ctx - C, w.n_ctx
+    K, V = vsgen.make_kv(w, n_k, device=dev)
+    Q = vsgen.make_q(w, s, n_k, device=dev)
+    pb = oracle.Problem(w.n_q_heads, w.n_kv_heads, w.head_dim, C, s, w.softmax_scale, last_q=w.last_q,
+                        vertical_budget=w.vertical_budget, slash_budget=w.slash_budget,
+                        keep_first_cols=w.keep_first_cols, keep_local_band=w.keep_local_band)
+    ck = chunk_of(pb)
+    vsc, ssc, _ = vs.estimate(ck, Q, K)
+    sets = vs.select(ck, vsc, ssc)
+    out_s, lse_s = vs.sparse_attn_prefill(ck, Q, K, V, *sets, want_lse=True)
+    out_d, lse_d = vs.dense_causal_prefill(ck, Q, K, V, want_lse=True)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(2400 + C)
+    heads = np.array([0, 5, 13, 27])
+    rows = np.array(sorted(set([0, C - 1] + rng.choice(C, min(4, C), replace=False).tolist())))
+    qh, kh, vh = vsgen.as_u16(Q), vsgen.as_u16(K), vsgen.as_u16(V)
+    ref_out, ref_lse = oracle.dense_attention(pb, qh, kh, vh, heads=heads, rows=rows)
+    _check_rows(out_d, lse_d, ref_out, ref_lse, heads, rows, f"dense, {C} rows at 1M keys")
+    sh = [x.cpu().numpy() for x in sets]
+    ref_out, ref_lse = oracle.sparse_attention(pb, qh, kh, vh, *sh, heads=heads, rows=rows)
+    _check_rows(out_s, lse_s, ref_out, ref_lse, heads, rows, f"sparse, {C} rows at 1M keys")
