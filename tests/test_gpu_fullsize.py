@@ -154,6 +154,12 @@ def test_sparse_7b_1m_middle_chunk():
     _run_sparse_chunk("7b_1m", 15, heads=[11], n_rows=8, seed=4)
 
 
+def test_sparse_7b_1m_first_chunks():
+    # the first chunks of the whole-layer run: no keys before the chunk; budgets that cover nearly every diagonal
+    _run_sparse_chunk("7b_1m", 0, heads=[2, 25], n_rows=8, seed=8)
+    _run_sparse_chunk("7b_1m", 1, heads=[14], n_rows=8, seed=9)
+
+
 def test_sparse_14b_1m_last_chunk():
     _run_sparse_chunk("14b_1m", -1, heads=[7, 38], n_rows=8, seed=5)            # configuration 4
 
