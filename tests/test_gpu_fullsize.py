@@ -160,6 +160,12 @@ def test_sparse_7b_1m_first_chunks():
     _run_sparse_chunk("7b_1m", 1, heads=[14], n_rows=8, seed=9)
 
 
+def test_sparse_7b_1m_local_last_chunk():
+    # the clustered regime (slashes close to the diagonal, as real attention maps have them): 11 % of the blocks,
+    # long sync segments, short lists
+    _run_sparse_chunk("7b_1m_local", -1, heads=[1, 19], n_rows=8, seed=10)
+
+
 def test_sparse_14b_1m_last_chunk():
     _run_sparse_chunk("14b_1m", -1, heads=[7, 38], n_rows=8, seed=5)            # configuration 4
 
